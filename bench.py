@@ -1,0 +1,119 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused attention forward + JVP on one MI355X.
+
+A "step" is one call of attn_jvp_fwd (the whole hot path: Q/tQ load, KV streaming, six contractions,
+online softmax, epilogue) on one batch of synthetic input already resident in HBM.
+Prints ONE JSON line: attention+JVP TFLOP/s counting 12*Lq*Lkv*d flops per head, the roofline of the
+(single) kernel against the bf16 dense MFMA peak, and the fp64 CPU oracle timed on a bounded row sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: video-DiT self-attention)")
+    ap.add_argument("--fast", action="store_true", help="time the single-bf16 H~ variant instead of the default")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "hbm_traffic.json"),
+                    help="optional file with measured HBM bytes per launch, {workload: bytes}")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2510_08431_amd import binding
+    from paper_2510_08431_amd.workloads import CONFIGS, make_inputs, make_head, sample_rows
+
+    binding.load_library()          # fails loudly when the HIP library is missing
+    cfg = CONFIGS[args.config]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t = {n: x.to(dev) for n, x in make_inputs(cfg).items()}
+    B, H, Lq, Lkv, d = cfg.B, cfg.H, cfg.Lq, cfg.Lkv, cfg.d
+    o = torch.empty(B, H, Lq, d, dtype=torch.float32, device=dev)
+    to = torch.empty_like(o)
+    lse = torch.empty(B, H, Lq, dtype=torch.float32, device=dev)
+    flags = binding.FLAG_FAST if args.fast else 0
+
+    def step():
+        binding.attn_jvp_fwd_ex(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], cfg.scale, out=(o, to, lse),
+                                flags=flags)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # whole-job wall clock over exactly K steps, plus per-launch HIP-event times on the launch stream
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in evs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [a.elapsed_time(b) for a, b in evs]
+    ms_per_step = wall * 1e3 / args.steps
+    kern_avg_ms = float(np.mean(kern_ms))
+    tflops = cfg.flops / (ms_per_step * 1e-3) / 1e12
+    kern_tflops = cfg.flops / (kern_avg_ms * 1e-3) / 1e12
+
+    traffic = None
+    try:
+        with open(args.traffic_json) as f:
+            traffic = json.load(f).get(cfg.name)
+    except OSError:
+        pass
+
+    out = {
+        "metric": "attention+JVP TFLOP/s (bf16, 12*Lq*Lkv*d/head)", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
+                   "variant": "fast" if args.fast else "default"},
+        "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                     "kernel": "attn_jvp_mfma_kernel" if cfg.dtype == "bf16" and d == 128 else "attn_jvp_fp32_kernel",
+                     "kernel_ms_avg": round(kern_avg_ms, 4), "kernel_ms_min": round(float(np.min(kern_ms)), 4)},
+    }
+
+    if not args.no_cpu_baseline:
+        # the fp64 oracle, as it stands, on a bounded sample of the same workload: a seeded set of query rows
+        # (all keys) of the first few heads, sized for roughly 10-20 s of host work
+        from oracle.attn_jvp_ref import attn_jvp_ref
+        rows_per_head = min(Lq, max(16, int(1.6e11 / (12.0 * Lkv * d))))
+        n_heads = min(B * H, 6)
+        rows = sample_rows(cfg, rows_per_head)[:rows_per_head]
+        heads = [{n: x[None, None] for n, x in make_head(cfg, i // H, i % H).items()} for i in range(n_heads)]
+        attn_jvp_ref(*(heads[0][n] for n in ("q", "k", "v", "tq", "tk", "tv")), cfg.scale, rows=rows[:8])
+        c0 = time.perf_counter()
+        for hd in heads:
+            attn_jvp_ref(hd["q"], hd["k"], hd["v"], hd["tq"], hd["tk"], hd["tv"], cfg.scale, rows=rows)
+        cpu_s = time.perf_counter() - c0
+        n_eval = len(rows) * n_heads
+        cpu_tflops = 12.0 * n_eval * Lkv * d / cpu_s / 1e12
+        out["cpu_baseline"] = {"value": round(cpu_tflops, 5), "unit": "TFLOP/s", "cores": torch.get_num_threads(),
+                               "kind": "oracle",
+                               "sample": f"{len(rows)} query rows x all {Lkv} keys of each of {n_heads} heads, fp64 numpy, {cpu_s:.1f} s",
+                               "full_workload_s_extrapolated": round(cfg.flops / (cpu_tflops * 1e12), 1)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,98 @@
+/*
+ * attn_jvp.h - C ABI of the MI355X (gfx950) fused attention forward + Jacobian-vector product.
+ *
+ * Operation (paper App. C.1: the equations defining S, P, O and tS, tP, tO; Alg. 2 is the
+ * streaming procedure that evaluates them without forming the Lq x Lkv matrices).
+ * Per (batch b, head h), with s = `scale`:
+ *
+ *     S  = s Q K^T            P  = softmax_rows(S)          O  = P V
+ *     tS = s (tQ K^T + Q tK^T)
+ *     tP = P o tS - P o rowsum(P o tS)                      tO = tP V + P tV
+ *     lse_i = log sum_j exp(S_ij)                           (the L of Alg. 2's epilogue)
+ *
+ * Non-causal, no mask, no dropout; Lq and Lkv are independent (self- and cross-attention).
+ * The paper writes S = Q K^T without a softmax scale; here the caller's constant `scale`
+ * multiplies both S and tS.
+ *
+ * Memory: every pointer is a DEVICE pointer owned by the caller; the library allocates
+ * nothing, keeps no state between calls and needs no workspace.
+ *   q, tq        [B, H, Lq,  d]  contiguous, row-major, d fastest
+ *   k, v, tk, tv [B, H, Lkv, d]  same
+ *   o, to        [B, H, Lq,  d]  float32 (or the input dtype, see attn_jvp_opts.out_dtype)
+ *   lse          [B, H, Lq]      float32, natural log
+ * Inputs are never written.  Outputs must not alias inputs or one another.  All pointers
+ * must be 16-byte aligned.
+ *
+ * Execution: a call validates its arguments on the host, enqueues the kernel on the given
+ * HIP stream and returns without synchronising.  A return value of 0 means "enqueued".
+ * On any non-zero return nothing was launched and the outputs are untouched.  No exception
+ * or abort crosses this boundary.  Results are deterministic (no atomics).
+ */
+#ifndef ATTN_JVP_H_
+#define ATTN_JVP_H_
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* error codes */
+#define ATTN_JVP_OK            0
+#define ATTN_JVP_NULL_PTR      1  /* a required pointer is NULL */
+#define ATTN_JVP_BAD_SHAPE     2  /* B, H, Lq, Lkv or d <= 0, a product overflows, or scale is not finite */
+#define ATTN_JVP_UNSUPPORTED   3  /* head dim / dtype / kernel choice not built */
+#define ATTN_JVP_MISALIGNED    4  /* a pointer is not 16-byte aligned */
+#define ATTN_JVP_LAUNCH_FAILED 5  /* the HIP runtime refused the launch */
+
+/* attn_jvp_opts.in_dtype / out_dtype */
+#define ATTN_JVP_BF16 0
+#define ATTN_JVP_FP32 1
+#define ATTN_JVP_OUT_FP32  0      /* o, to are float32 (default; the accumulators' own precision) */
+#define ATTN_JVP_OUT_INPUT 1      /* o, to have the input dtype */
+
+/* attn_jvp_opts.kernel */
+#define ATTN_JVP_KERNEL_AUTO 0    /* bf16 d=128 -> MFMA kernel; everything else -> fp32 vector kernel */
+#define ATTN_JVP_KERNEL_FP32 1    /* fp32 vector-ALU streaming kernel: any dtype, d in {32, 64, 128, 256}, slow */
+#define ATTN_JVP_KERNEL_MFMA 2    /* bf16 matrix-core kernel: bf16 inputs, d = 128 */
+
+/* attn_jvp_opts.flags */
+#define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only: round the weights P~ and H~ = P~ o tS to ONE bf16 term each
+                                     (6 matrix products per key tile, as Alg. 2 counts them) instead of the default
+                                     hi + lo bf16 pairs for the O and B contractions (8 products).  Faster; the 8-bit
+                                     rounding then shows in the results: max errors around 1e-2 of RMS(O) and up to
+                                     a few 1e-2 of RMS(tO) on rows where few keys carry the weight. */
+
+typedef struct attn_jvp_opts {
+    int   in_dtype;   /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
+    int   out_dtype;  /* ATTN_JVP_OUT_FP32 or ATTN_JVP_OUT_INPUT: dtype of o, to */
+    void* stream;     /* hipStream_t; NULL = the default stream */
+    int   kernel;     /* ATTN_JVP_KERNEL_* */
+    int   flags;      /* bitwise OR of ATTN_JVP_FLAG_*; unknown bits are rejected */
+    int   reserved[3];/* must be zero */
+} attn_jvp_opts;
+
+/*
+ * Alg. 2 with bf16 inputs, float32 o/to/lse, on the default stream, kernel chosen automatically.
+ * Returns ATTN_JVP_OK or an error code above.
+ */
+int attn_jvp_fwd(const void* q, const void* k, const void* v,
+                 const void* tq, const void* tk, const void* tv,
+                 void* o, void* to, float* lse,
+                 int B, int H, int Lq, int Lkv, int d, float scale);
+
+/* Same operation with explicit dtype, stream and kernel choice. opts == NULL means the defaults of attn_jvp_fwd. */
+int attn_jvp_fwd_ex(const void* q, const void* k, const void* v,
+                    const void* tq, const void* tk, const void* tv,
+                    void* o, void* to, float* lse,
+                    int B, int H, int Lq, int Lkv, int d, float scale,
+                    const attn_jvp_opts* opts);
+
+/* Static, NUL-terminated description of an error code (never NULL). */
+const char* attn_jvp_strerror(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int attn_jvp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ATTN_JVP_H_ */

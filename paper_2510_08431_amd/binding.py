@@ -1,0 +1,121 @@
+"""ctypes binding of the attn_jvp C-ABI library: argument marshalling only.
+
+PyTorch supplies device memory (`data_ptr()`) and the current HIP stream; every step of
+the computation runs inside the library's kernels.  There is no CPU or eager fallback:
+if the shared library is missing, loading raises.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libattn_jvp.so")
+
+KERNEL_AUTO, KERNEL_FP32, KERNEL_MFMA = 0, 1, 2
+FLAG_FAST = 1   # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key tile instead of 8)
+_DTYPE_CODE = {torch.bfloat16: 0, torch.float32: 1}
+
+
+class AttnJvpOpts(ctypes.Structure):
+    _fields_ = [("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int), ("stream", ctypes.c_void_p),
+                ("kernel", ctypes.c_int), ("flags", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+
+
+class AttnJvpError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"attn_jvp error {code}: {message}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load libattn_jvp.so (built in-tree by __graft_entry__.build()) and declare its symbols."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build the HIP library first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    common = [vp] * 9 + [ci] * 5 + [cf]
+    lib.attn_jvp_fwd.argtypes = common
+    lib.attn_jvp_fwd.restype = ci
+    lib.attn_jvp_fwd_ex.argtypes = common + [ctypes.POINTER(AttnJvpOpts)]
+    lib.attn_jvp_fwd_ex.restype = ci
+    lib.attn_jvp_strerror.argtypes = [ci]
+    lib.attn_jvp_strerror.restype = ctypes.c_char_p
+    lib.attn_jvp_version.argtypes = []
+    lib.attn_jvp_version.restype = ci
+    _lib = lib
+    return lib
+
+
+def attn_jvp_strerror(code):
+    return load_library().attn_jvp_strerror(int(code)).decode()
+
+
+def attn_jvp_version():
+    return load_library().attn_jvp_version()
+
+
+def _check_inputs(q, k, v, tq, tk, tv):
+    if q.dim() != 4:
+        raise ValueError("q must be [B, H, Lq, d]")
+    B, H, Lq, d = q.shape
+    Lkv = k.shape[2]
+    for name, t, L in (("q", q, Lq), ("tq", tq, Lq), ("k", k, Lkv), ("v", v, Lkv), ("tk", tk, Lkv), ("tv", tv, Lkv)):
+        if tuple(t.shape) != (B, H, L, d):
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {(B, H, L, d)}")
+        if t.dtype != q.dtype or t.device != q.device:
+            raise ValueError(f"{name}: dtype/device differ from q")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous [B, H, L, d]")
+    if q.dtype not in _DTYPE_CODE:
+        raise ValueError(f"unsupported dtype {q.dtype}")
+    if not q.is_cuda:
+        raise ValueError("tensors must live on the GPU; there is no CPU path")
+    return B, H, Lq, Lkv, d
+
+
+def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float32, kernel=KERNEL_AUTO, stream=None,
+                    flags=0):
+    """Enqueue O, tO, lse = attention forward + JVP on the current (or given) stream.
+
+    q, tq: [B, H, Lq, d]; k, v, tk, tv: [B, H, Lkv, d]; bf16 or fp32, contiguous, on the GPU.
+    out: optional (o, to, lse) to write into.  Returns (o, to, lse); asynchronous.
+    """
+    lib = load_library()
+    B, H, Lq, Lkv, d = _check_inputs(q, k, v, tq, tk, tv)
+    if out is None:
+        o = torch.empty(B, H, Lq, d, dtype=out_dtype, device=q.device)
+        to = torch.empty_like(o)
+        lse = torch.empty(B, H, Lq, dtype=torch.float32, device=q.device)
+    else:
+        o, to, lse = out
+        out_dtype = o.dtype
+    if out_dtype not in (torch.float32, q.dtype):
+        raise ValueError("out_dtype must be float32 or the input dtype")
+    opts = AttnJvpOpts()
+    opts.in_dtype = _DTYPE_CODE[q.dtype]
+    opts.out_dtype = 0 if out_dtype == torch.float32 else 1
+    if stream is None:
+        stream = torch.cuda.current_stream(q.device)
+    opts.stream = stream.cuda_stream
+    opts.kernel = int(kernel)
+    opts.flags = int(flags)
+    with torch.cuda.device(q.device):
+        rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
+                                 o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale),
+                                 ctypes.byref(opts))
+    if rc != 0:
+        raise AttnJvpError(rc, attn_jvp_strerror(rc))
+    return o, to, lse
+
+
+def attn_jvp_fwd(q, k, v, tq, tk, tv, scale, out=None):
+    """The C entry point `attn_jvp_fwd`: bf16 inputs, fp32 outputs, automatic kernel choice."""
+    return attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=out)

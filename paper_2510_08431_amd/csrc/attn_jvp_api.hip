@@ -1,0 +1,85 @@
+// C-ABI entry points: argument validation, kernel choice, launch.  No allocation, no state.
+#include "../../include/attn_jvp.h"
+#include "launchers.h"
+#include <cmath>
+#include <cstdint>
+
+using attn_jvp::Problem;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int run(const void* q, const void* k, const void* v, const void* tq, const void* tk, const void* tv,
+        void* o, void* to, float* lse, int B, int H, int Lq, int Lkv, int d, float scale,
+        const attn_jvp_opts* opts) {
+    attn_jvp_opts def = {};
+    def.in_dtype = ATTN_JVP_BF16;
+    def.out_dtype = ATTN_JVP_OUT_FP32;
+    if (!opts) opts = &def;
+
+    if (!q || !k || !v || !tq || !tk || !tv || !o || !to || !lse) return ATTN_JVP_NULL_PTR;
+    if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0 || d <= 0) return ATTN_JVP_BAD_SHAPE;
+    if (!std::isfinite(scale)) return ATTN_JVP_BAD_SHAPE;
+    // element counts must stay far below 2^62 so that byte offsets fit in 64 bits; B*H must fit a grid dimension
+    const long double elems = (long double)B * H * (long double)(Lq > Lkv ? Lq : Lkv) * d;
+    if (elems > 4.0e18L || (long long)B * H > 0x7fffffffLL) return ATTN_JVP_BAD_SHAPE;
+    if (opts->in_dtype != ATTN_JVP_BF16 && opts->in_dtype != ATTN_JVP_FP32) return ATTN_JVP_UNSUPPORTED;
+    if (opts->out_dtype != ATTN_JVP_OUT_FP32 && opts->out_dtype != ATTN_JVP_OUT_INPUT) return ATTN_JVP_UNSUPPORTED;
+    for (int i = 0; i < 3; ++i)
+        if (opts->reserved[i] != 0) return ATTN_JVP_UNSUPPORTED;
+    if (opts->flags & ~ATTN_JVP_FLAG_FAST) return ATTN_JVP_UNSUPPORTED;
+    const void* ptrs[] = {q, k, v, tq, tk, tv, o, to, lse};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return ATTN_JVP_MISALIGNED;
+
+    Problem p{q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale,
+              opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags};
+
+    int kernel = opts->kernel;
+    if (kernel == ATTN_JVP_KERNEL_AUTO)
+        kernel = attn_jvp::mfma_bf16_supports(p) ? ATTN_JVP_KERNEL_MFMA : ATTN_JVP_KERNEL_FP32;
+
+    hipError_t e;
+    if (kernel == ATTN_JVP_KERNEL_MFMA) {
+        if (!attn_jvp::mfma_bf16_supports(p)) return ATTN_JVP_UNSUPPORTED;
+        e = attn_jvp::launch_mfma_bf16(p);
+    } else if (kernel == ATTN_JVP_KERNEL_FP32) {
+        if (!attn_jvp::fp32_vector_supports(p)) return ATTN_JVP_UNSUPPORTED;
+        e = attn_jvp::launch_fp32_vector(p);
+    } else {
+        return ATTN_JVP_UNSUPPORTED;
+    }
+    return e == hipSuccess ? ATTN_JVP_OK : ATTN_JVP_LAUNCH_FAILED;
+}
+
+}  // namespace
+
+extern "C" {
+
+int attn_jvp_fwd(const void* q, const void* k, const void* v, const void* tq, const void* tk, const void* tv,
+                 void* o, void* to, float* lse, int B, int H, int Lq, int Lkv, int d, float scale) {
+    return run(q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale, nullptr);
+}
+
+int attn_jvp_fwd_ex(const void* q, const void* k, const void* v, const void* tq, const void* tk, const void* tv,
+                    void* o, void* to, float* lse, int B, int H, int Lq, int Lkv, int d, float scale,
+                    const attn_jvp_opts* opts) {
+    return run(q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale, opts);
+}
+
+const char* attn_jvp_strerror(int code) {
+    switch (code) {
+        case ATTN_JVP_OK: return "ok";
+        case ATTN_JVP_NULL_PTR: return "a required pointer is NULL";
+        case ATTN_JVP_BAD_SHAPE: return "a dimension is not positive, the shape is too large, or scale is not finite";
+        case ATTN_JVP_UNSUPPORTED: return "unsupported head dim, dtype, kernel choice or option";
+        case ATTN_JVP_MISALIGNED: return "a pointer is not 16-byte aligned";
+        case ATTN_JVP_LAUNCH_FAILED: return "the HIP runtime refused the kernel launch";
+        default: return "unknown attn_jvp error code";
+    }
+}
+
+int attn_jvp_version(void) { return 100; }  // 0.1.0
+
+}  // extern "C"

@@ -1,0 +1,210 @@
+"""Parity of the HIP path (through the C-ABI) against the fp64 CPU oracle, element by element.
+
+Metric: max |x - x_ref| / RMS(x_ref) over the compared elements.
+Tolerances (the task's): fp32 inputs 1e-5 for O and tO; bf16 inputs 1e-2 for O, 2e-2 for tO.
+lse: absolute 1e-5 (fp32) / 1e-3 (bf16).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.attn_jvp_ref import attn_jvp_ref
+from paper_2510_08431_amd import binding
+from paper_2510_08431_amd.workloads import CONFIGS, make_head, make_inputs, sample_rows
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+TOL = {torch.float32: (1e-5, 1e-5, 1e-5), torch.bfloat16: (1e-2, 2e-2, 1e-3)}
+
+
+def rel_err(x, ref):
+    return float(np.abs(x - ref).max() / max(np.sqrt((ref ** 2).mean()), 1e-300))
+
+
+def run_gpu(t, scale, kernel=binding.KERNEL_AUTO, flags=0):
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    o, to, lse = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                         kernel=kernel, flags=flags)
+    torch.cuda.synchronize()
+    return o.cpu().double().numpy(), to.cpu().double().numpy(), lse.cpu().double().numpy()
+
+
+def compare(got, ref, dtype, label, rows=None, tol=None):
+    o, to, lse = got
+    if rows is not None:
+        o, to, lse = o[:, :, rows], to[:, :, rows], lse[:, :, rows]
+    o_ref, to_ref, lse_ref = ref
+    tol_o, tol_to, tol_lse = tol or TOL[dtype]
+    e_o, e_to, e_lse = rel_err(o, o_ref), rel_err(to, to_ref), float(np.abs(lse - lse_ref).max())
+    print(f"[{label}] err O={e_o:.3e} tO={e_to:.3e} lse={e_lse:.3e}", flush=True)
+    assert np.isfinite(o).all() and np.isfinite(to).all() and np.isfinite(lse).all(), label
+    assert e_o <= tol_o, f"{label}: O error {e_o}"
+    assert e_to <= tol_to, f"{label}: tO error {e_to}"
+    assert e_lse <= tol_lse, f"{label}: lse error {e_lse}"
+    return e_o, e_to
+
+
+def random_inputs(seed, B, H, Lq, Lkv, d, dtype, tangent_std=0.5, qk_gain=1.0):
+    g = torch.Generator().manual_seed(seed)
+    mk = lambda L, s: (s * torch.randn(B, H, L, d, generator=g)).to(dtype)
+    return {"q": mk(Lq, qk_gain), "k": mk(Lkv, qk_gain), "v": mk(Lkv, 1.0),
+            "tq": mk(Lq, tangent_std), "tk": mk(Lkv, tangent_std), "tv": mk(Lkv, tangent_std)}
+
+
+def check_full(t, scale, kernel, label, flags=0, tol=None):
+    got = run_gpu(t, scale, kernel, flags)
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    return compare(got, ref, t["q"].dtype, label, tol=tol)
+
+
+# ------------------------------------------------------------------ fp32 vector kernel
+
+def test_config1_tiny_fp32():
+    cfg = CONFIGS[1]
+    t = make_inputs(cfg)
+    check_full(t, cfg.scale, binding.KERNEL_AUTO, "cfg1 fp32 auto")
+
+
+@pytest.mark.parametrize("d", [32, 64, 128, 256])
+@pytest.mark.parametrize("Lq,Lkv", [(1, 1), (70, 45), (64, 32), (130, 257)])
+def test_fp32_kernel_shapes(d, Lq, Lkv):
+    t = random_inputs(100 + d + Lq, 2, 2, Lq, Lkv, d, torch.float32, tangent_std=1.0)
+    check_full(t, d ** -0.5, binding.KERNEL_FP32, f"fp32 d={d} Lq={Lq} Lkv={Lkv}")
+
+
+def test_fp32_kernel_with_bf16_inputs():
+    t = random_inputs(7, 1, 3, 150, 200, 128, torch.bfloat16)
+    got = run_gpu(t, 128 ** -0.5, binding.KERNEL_FP32)
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], 128 ** -0.5)
+    # bf16 inputs are exact in fp32 and the arithmetic is fp32: the fp32 tolerance applies
+    compare(got, ref, torch.float32, "fp32 kernel, bf16 inputs")
+
+
+# ------------------------------------------------------------------ bf16 MFMA kernel: shapes and edge cases
+
+@pytest.mark.parametrize("Lq,Lkv", [(1, 1), (32, 64), (128, 64), (128, 65), (200, 333), (129, 127), (31, 1000),
+                                    (517, 4), (384, 640)])
+def test_mfma_kernel_shapes(Lq, Lkv):
+    t = random_inputs(300 + Lq + Lkv, 2, 3, Lq, Lkv, 128, torch.bfloat16)
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, f"mfma Lq={Lq} Lkv={Lkv}")
+
+
+# The FAST variant rounds P~ and H~ to single bf16 terms (relative rounding error up to 2^-8 per weight).  Its
+# error is heavy-tailed on rows where a handful of keys carry the weight (one product P~ (tS - ctr) V can
+# dominate), so it is held to a looser envelope than the default variant: 1.5e-2 of RMS(O), 6e-2 of RMS(tO).
+FAST_TOL = (1.5e-2, 6e-2, 1e-3)
+
+
+@pytest.mark.parametrize("Lq,Lkv", [(1, 1), (128, 65), (200, 333), (517, 4), (384, 640)])
+def test_mfma_fast_variant_shapes(Lq, Lkv):
+    t = random_inputs(300 + Lq + Lkv, 2, 3, Lq, Lkv, 128, torch.bfloat16)
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, f"mfma-fast Lq={Lq} Lkv={Lkv}", flags=binding.FLAG_FAST,
+               tol=FAST_TOL)
+
+
+def test_mfma_fast_variant_config3_sample():
+    cfg = CONFIGS[3]
+    t = {n: x[None, None] for n, x in make_head(cfg, 0, 7).items()}
+    got = run_gpu(t, cfg.scale, binding.KERNEL_MFMA, binding.FLAG_FAST)
+    rows = sample_rows(cfg, 256)
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], cfg.scale, rows=rows)
+    compare(got, ref, cfg.torch_dtype, "cfg3 head 7 fast", rows=rows, tol=(1.5e-2, 2e-2, 1e-3))
+
+
+def test_mfma_default_entry_point_and_preallocated_outputs():
+    t = random_inputs(11, 1, 2, 300, 260, 128, torch.bfloat16)
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    scale = 128 ** -0.5
+    o1, to1, lse1 = binding.attn_jvp_fwd(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale)
+    torch.cuda.synchronize()
+    out = (torch.full_like(o1, float("nan")), torch.full_like(to1, float("nan")), torch.full_like(lse1, float("nan")))
+    binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale, out=out,
+                            kernel=binding.KERNEL_MFMA)
+    torch.cuda.synchronize()
+    # same kernel, same inputs: bit-identical (no atomics, fixed summation order)
+    assert torch.equal(o1, out[0]) and torch.equal(to1, out[1]) and torch.equal(lse1, out[2])
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    compare((o1.cpu().double().numpy(), to1.cpu().double().numpy(), lse1.cpu().double().numpy()), ref,
+            torch.bfloat16, "default entry point")
+
+
+def test_mfma_structured_tangents():
+    B, H, Lq, Lkv, d = 1, 2, 260, 450, 128
+    scale = d ** -0.5
+    t = random_inputs(21, B, H, Lq, Lkv, d, torch.bfloat16)
+    z = lambda x: torch.zeros_like(x)
+    # zero tangents: tO is exactly zero
+    t0 = dict(t, tq=z(t["tq"]), tk=z(t["tk"]), tv=z(t["tv"]))
+    o, to, _ = run_gpu(t0, scale, binding.KERNEL_MFMA)
+    assert np.all(to == 0.0)
+    # tV = V, tQ = tK = 0: tO = O.  In the FAST variant both come from the same products in the same order
+    # (bit-identical); the default variant gives O the extra low-order term of P~, so they agree to rounding.
+    t1 = dict(t0, tv=t["v"])
+    o, to, _ = run_gpu(t1, scale, binding.KERNEL_MFMA, binding.FLAG_FAST)
+    np.testing.assert_array_equal(to, o)
+    o, to, _ = run_gpu(t1, scale, binding.KERNEL_MFMA)
+    assert rel_err(to, o) <= 1e-2
+    # every key gets the same tangent vector u (tQ = tV = 0): tS is constant along each row, so tO = 0;
+    # the kernel reaches it by cancelling B against r*O, which stresses the bf16 rounding of H~
+    u = torch.randn(d, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
+    t2 = dict(t0, tk=u.expand(B, H, Lkv, d).contiguous())
+    got = run_gpu(t2, scale, binding.KERNEL_MFMA)
+    ref = attn_jvp_ref(t2["q"], t2["k"], t2["v"], t2["tq"], t2["tk"], t2["tv"], scale)
+    o_rms = np.sqrt((ref[0] ** 2).mean())
+    ts_rms = float((t["q"].double() @ u.double()).pow(2).mean().sqrt()) * scale
+    err = np.abs(got[1]).max() / (o_rms * ts_rms)
+    print(f"[row-constant tS] |tO|max / (rms O * rms tS) = {err:.3e}", flush=True)
+    assert err <= 2e-2
+
+
+def test_mfma_peaked_softmax_small():
+    """Logit std ~8 (one key dominates most rows) on a shape the oracle does in full."""
+    t = random_inputs(31, 1, 2, 256, 2048, 128, torch.bfloat16, tangent_std=1.0, qk_gain=8 ** 0.5)
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "peaked softmax L=2048")
+
+
+# ------------------------------------------------------------------ the five named configurations
+
+def check_config_sampled(cfg, n_random, heads=None):
+    """Full-size launch; oracle on a seeded sample of query rows of every (or the given) head."""
+    t = make_inputs(cfg)
+    got = run_gpu(t, cfg.scale)
+    rows = sample_rows(cfg, n_random)
+    worst = [0.0, 0.0]
+    for b in range(cfg.B):
+        for h in (heads if heads is not None else range(cfg.H)):
+            sl = lambda x: x[b:b + 1, h:h + 1]
+            ref = attn_jvp_ref(sl(t["q"]), sl(t["k"]), sl(t["v"]), sl(t["tq"]), sl(t["tk"]), sl(t["tv"]),
+                               cfg.scale, rows=rows)
+            g = tuple(x[b:b + 1, h:h + 1] for x in got)
+            e = compare(g, ref, cfg.torch_dtype, f"cfg{cfg.idx} b{b} h{h}", rows=rows)
+            worst = [max(worst[0], e[0]), max(worst[1], e[1])]
+    print(f"[cfg{cfg.idx}] worst err O={worst[0]:.3e} tO={worst[1]:.3e}", flush=True)
+
+
+def test_config2_image_dit():
+    check_config_sampled(CONFIGS[2], 256)
+
+
+def test_config2_image_dit_one_head_all_rows():
+    cfg = CONFIGS[2]
+    t = {n: x.unsqueeze(0).unsqueeze(0) for n, x in make_head(cfg, 1, 5).items()}
+    check_full(t, cfg.scale, binding.KERNEL_AUTO, "cfg2 head (1,5) all rows")
+
+
+def test_config3_video_self():
+    check_config_sampled(CONFIGS[3], 96)
+
+
+def test_config4_video_cross_all_rows():
+    cfg = CONFIGS[4]
+    t = make_inputs(cfg)
+    got = run_gpu(t, cfg.scale)
+    for h in range(cfg.H):
+        sl = lambda x: x[:, h:h + 1]
+        ref = attn_jvp_ref(sl(t["q"]), sl(t["k"]), sl(t["v"]), sl(t["tq"]), sl(t["tk"]), sl(t["tv"]), cfg.scale)
+        compare(tuple(x[:, h:h + 1] for x in got), ref, cfg.torch_dtype, f"cfg4 h{h}")
+
+
+def test_config5_video_14b_stress():
+    check_config_sampled(CONFIGS[5], 64)

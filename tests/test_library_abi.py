@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, and turns invalid arguments into error codes before anything is launched."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "attn_jvp.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2510_08431_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(attn_jvp_\w+)\s*\(", text)))
+
+
+def test_header_symbols_exported(lib):
+    names = declared_functions()
+    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_strerror", "attn_jvp_version"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def test_version_and_strerror(lib):
+    assert lib.attn_jvp_version() >= 100
+    msgs = [lib.attn_jvp_strerror(c).decode() for c in range(0, 7)]
+    assert msgs[0] == "ok" and len(set(msgs)) == 7 and all(msgs)
+
+
+def _call(lib, ptrs=None, dims=(1, 1, 8, 8, 128), scale=0.1, opts=None):
+    p = [0x1000 * (i + 1) for i in range(9)] if ptrs is None else ptrs
+    args = [ctypes.c_void_p(x) for x in p] + list(dims) + [ctypes.c_float(scale)]
+    if opts is None:
+        return lib.attn_jvp_fwd(*args)
+    return lib.attn_jvp_fwd_ex(*args, ctypes.byref(opts))
+
+
+def test_argument_validation_returns_codes_without_launching(lib):
+    """Fake (never dereferenced) addresses: every call here must be rejected on the host."""
+    from paper_2510_08431_amd.binding import AttnJvpOpts
+    good = [0x1000 * (i + 1) for i in range(9)]
+    for i in range(9):
+        p = list(good); p[i] = 0
+        assert _call(lib, p) == 1                         # NULL_PTR
+    for i in range(5):
+        for bad in (0, -3):
+            dims = [1, 1, 8, 8, 128]; dims[i] = bad
+            assert _call(lib, dims=dims) == 2             # BAD_SHAPE
+    assert _call(lib, scale=float("nan")) == 2
+    assert _call(lib, scale=float("inf")) == 2
+    assert _call(lib, dims=(1, 1, 8, 8, 48)) == 3         # UNSUPPORTED head dim
+    for i in range(9):
+        p = list(good); p[i] += 8
+        assert _call(lib, p) == 4                         # MISALIGNED
+    o = AttnJvpOpts(); o.in_dtype = 7
+    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.out_dtype = 5
+    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.kernel = 9
+    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.reserved[2] = 1
+    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.kernel = 2; o.in_dtype = 1        # MFMA kernel with fp32 inputs
+    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.kernel = 2                        # MFMA kernel with d = 64
+    assert _call(lib, dims=(1, 1, 8, 8, 64), opts=o) == 3
+
+
+def test_binding_rejects_cpu_tensors_and_bad_shapes():
+    import torch
+    from paper_2510_08431_amd import binding
+    q = torch.zeros(1, 1, 4, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        binding.attn_jvp_fwd(q, q, q, q, q, q, 0.1)       # CPU tensors: no CPU path exists
+    with pytest.raises(ValueError):
+        binding._check_inputs(q, q, q, q, q, q[:, :, :2])
+    with pytest.raises(ValueError):
+        binding._check_inputs(q, q, q.float(), q, q, q)
+
+
+def test_workload_shapes_match_configs():
+    from paper_2510_08431_amd.workloads import CONFIGS, make_head, sample_rows
+    assert CONFIGS[3].Lq == 21 * 30 * 52 == 32760 and CONFIGS[5].Lq == 21 * 45 * 80 == 75600
+    assert abs(CONFIGS[3].flops - 1.978e13) / 1.978e13 < 1e-3
+    h = make_head(CONFIGS[1], 0, 1)
+    assert h["q"].shape == (256, 64) and h["q"].dtype.is_floating_point
+    h2 = make_head(CONFIGS[1], 0, 1)
+    assert all((h[k] == h2[k]).all() for k in h)          # seeded: reproducible
+    rows = sample_rows(CONFIGS[3], 64)
+    assert rows.min() == 0 and rows.max() == 32759 and len(set(rows.tolist())) == len(rows)
