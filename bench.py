@@ -26,6 +26,8 @@ def main():
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: video-DiT self-attention)")
     ap.add_argument("--fast", action="store_true", help="time the single-bf16 H~ variant instead of the default")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a plain 1 GiB device-to-device copy (known traffic) for scaling HBM counters")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "hbm_traffic.json"),
                     help="optional file with measured HBM bytes per launch, {workload: bytes}")
     args = ap.parse_args()
@@ -37,6 +39,18 @@ def main():
     import torch
     from paper_2510_08431_amd import binding
     from paper_2510_08431_amd.workloads import CONFIGS, make_inputs, make_head, sample_rows
+
+    if args.copy_calibration:
+        # a plain copy of known size: reads 1 GiB, writes 1 GiB per launch
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(3)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n, "launches": 3}))
+        return
 
     binding.load_library()          # fails loudly when the HIP library is missing
     cfg = CONFIGS[args.config]
