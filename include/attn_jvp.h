@@ -57,8 +57,8 @@ extern "C" {
 /* attn_jvp_opts.flags */
 #define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only: round the weights P~ and H~ = P~ o tS to ONE bf16 term each
                                      (6 matrix products per key tile, as Alg. 2 counts them) instead of the default
-                                     hi + lo bf16 pairs for the O and B contractions (8 products).  Faster; the 8-bit
-                                     rounding then shows in the results: max errors around 1e-2 of RMS(O) and up to
+                                     hi + lo bf16 pairs in all three value contractions (9 products).  Faster; the
+                                     8-bit rounding then shows in the results: max errors up to ~2e-2 of RMS(O) and
                                      a few 1e-2 of RMS(tO) on rows where few keys carry the weight. */
 
 typedef struct attn_jvp_opts {

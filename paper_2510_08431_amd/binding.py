@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libattn_jvp.so")
 
 KERNEL_AUTO, KERNEL_FP32, KERNEL_MFMA = 0, 1, 2
-FLAG_FAST = 1   # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key tile instead of 8)
+FLAG_FAST = 1   # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key tile instead of 9)
 _DTYPE_CODE = {torch.bfloat16: 0, torch.float32: 1}
 
 

@@ -1,61 +1,54 @@
-// bf16 matrix-core (MFMA) streaming kernel for attention forward + JVP (paper Alg. 2), d = 128.
-//
-// One workgroup = 4 wavefronts = 128 query rows; each wavefront owns 32 query rows for the whole
-// key/value sweep.  All six contractions of Alg. 2's inner loop run on v_mfma_f32_32x32x16_bf16
-// in the TRANSPOSED orientation: S^T = K Q^T, tS^T = K tQ^T + tK Q^T, O^T += V^T P~^T,
-// (A+B)^T += tV^T P~^T + V^T H~^T.  In that orientation a lane's MFMA result registers all belong
-// to ONE query (column = lane % 32), so
-//   * row max / row sums are in-lane reductions plus one exchange between lane l and l^32,
-//   * the rescale factor exp(m_old - m_new) is a per-lane scalar,
-//   * P~^T and H~^T feed the next MFMA as its B operand straight from registers (the contraction
-//     index - the key position - may be enumerated in any order as long as both operands agree,
-//     and V^T is fetched from LDS in exactly the order the result registers happen to hold).
-// A and B of Alg. 2 share one accumulator: they carry the same rescale factor and are only added.
-//
-// Key/value tiles (K, tK, V, tV: 64 rows x 128 bf16 each) are copied HBM -> LDS with 128-bit
-// direct-to-LDS loads, double buffered (2 x 64 KiB), XOR-swizzled so that both the row-wise
-// 128-bit reads (K, tK as MFMA A operand) and the transposing 64-bit reads (V, tV) spread over
-// all banks.  Q and tQ fragments stay in registers.
-//
-// Numerics: bf16 operands, fp32 accumulation; softmax in base 2 with scale*log2(e) folded into one
-// FMA; the running maximum m is raised only when some row's tile maximum exceeds it (wave-uniform
-// branch), which is Alg. 2's update whenever it fires and leaves m_new = m_old otherwise.
-// H~ = P~ o tS is formed as P~ o (tS - ctr) with a per-row constant ctr that follows the running value of
-// rowsum(P o tS): tP does not change when a constant is added to a row of tS, and a small |tS - ctr| on
-// the keys that carry the weight keeps the bf16 rounding of H~ from surviving the B - r O cancellation.
+// v2 experiment: manual software pipeline with scheduling fences (vgpr-form MFMA).
 #include "launchers.h"
 #include <hip/hip_bf16.h>
 #include <stdint.h>
+#include <type_traits>
+#include <utility>
 
 namespace attn_jvp {
 namespace {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
-typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int D = 128;
-constexpr int BR = 128;              // query rows per workgroup (32 per wavefront)
-constexpr int BC = 64;               // key rows per LDS stage
-constexpr int NTHREADS = 256;
-constexpr int ROW_BYTES = D * 2;     // 256
-constexpr int TILE_BYTES = BC * ROW_BYTES;   // 16 KiB per tensor per stage
-constexpr int STAGE_BYTES = 4 * TILE_BYTES;  // K, tK, V, tV
-constexpr int LDS_BYTES = 2 * STAGE_BYTES;   // 128 KiB
+constexpr int D = 128, BR = 128, BC = 32, NSTAGE = 4, NTHREADS = 256;
+constexpr int ROW_BYTES = D * 2;
+constexpr int TENSOR_BYTES = BC * ROW_BYTES;
+constexpr int STAGE_BYTES = 4 * TENSOR_BYTES;
+constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+constexpr int OFF_K = 0, OFF_TK = TENSOR_BYTES, OFF_V = 2 * TENSOR_BYTES, OFF_TV = 3 * TENSOR_BYTES;
 
-typedef __attribute__((address_space(3))) char lds_char;
+#define FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int N, typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl<N>(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
 
 __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
+#ifdef EXP_NO_LDS
+    u32x4 u = {addr, addr + 1, addr + 2, addr + 3};
+    return __builtin_bit_cast(bf16x8, u);
+#endif
     return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>((uintptr_t)addr);
 }
 __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t addr) {
+#ifdef EXP_NO_LDS
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_;
+    u32x2_ u = {addr, addr + 1};
+    return __builtin_bit_cast(s16x4, u);
+#endif
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         reinterpret_cast<__attribute__((address_space(3))) s16x4*>((uintptr_t)addr));
 }
-__device__ __forceinline__ float xhalf_max(float x) {   // max of lane l and lane l^32, in both
+__device__ __forceinline__ float xhalf_max(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
@@ -64,37 +57,42 @@ __device__ __forceinline__ float xhalf_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    bf16x2 v;
-    v[0] = (__bf16)lo;
-    v[1] = (__bf16)hi;
+    bf16x2 v; v[0] = (__bf16)lo; v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
 }
+__device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
+    u32x4 u = {a, b, c, d};
+    return __builtin_bit_cast(bf16x8, u);
+}
+__device__ __forceinline__ bf16x8 join_tr(s16x4 a, s16x4 b) {
+    return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
+}
 
-// Copy one 64-row tile of one tensor into LDS.  Each direct-to-LDS instruction moves 64 x 16 B =
-// 4 rows; the LDS side is linear in the lane id, so the swizzle is applied by choosing which
-// 16-byte chunk of the row each lane fetches.  vswz = false: chunk ^= row & 15 (row-wise b128
-// reads); vswz = true: chunk ^= (row & 3) << 2 (transposing b64 reads).  Rows past Lkv re-read
-// the last valid row (finite values; their scores are masked to -inf).
-template <bool VSWZ>
-__device__ __forceinline__ void issue_tile_load(const char* gbase, int j0, int Lkv, uint32_t lds_tensor_base,
-                                                int wave, int lane) {
+__device__ __forceinline__ void issue_block_load(const char* Kh, const char* tKh, const char* Vh, const char* tVh,
+                                                 int j0, int Lkv, uint32_t stage_base, int wave, int lane) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int rowblk = wave * 4 + i;
+    for (int i = 0; i < 2; ++i) {
+        const int rowblk = wave * 2 + i;
         const int row = rowblk * 4 + (lane >> 4);
         const int pc = lane & 15;
-        const int lc = VSWZ ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15));
         int grow = j0 + row;
         grow = grow < Lkv ? grow : Lkv - 1;
-        const char* g = gbase + (long)grow * ROW_BYTES + lc * 16;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                         (__attribute__((address_space(3))) void*)(uintptr_t)(lds_tensor_base + rowblk * 1024),
-                                         16, 0, 0);
+        const long goff_k = (long)grow * ROW_BYTES + ((pc ^ (row & 15)) << 4);
+        const long goff_v = (long)grow * ROW_BYTES + ((pc ^ ((row & 3) << 2)) << 4);
+        const uint32_t dst = stage_base + rowblk * 1024;
+#define ATTN_JVP_LOAD_LDS(g, l)                                                                        \
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g),               \
+                                     (__attribute__((address_space(3))) void*)(uintptr_t)(l), 16, 0, 0)
+        ATTN_JVP_LOAD_LDS(Kh + goff_k, dst + OFF_K);
+        ATTN_JVP_LOAD_LDS(tKh + goff_k, dst + OFF_TK);
+        ATTN_JVP_LOAD_LDS(Vh + goff_v, dst + OFF_V);
+        ATTN_JVP_LOAD_LDS(tVh + goff_v, dst + OFF_TV);
+#undef ATTN_JVP_LOAD_LDS
     }
 }
 
-// SPLIT: P~ (for O) and H~ (for B) enter their contractions as hi + lo bf16 terms, two more MFMAs per V fragment:
-// 8 matrix products per key tile instead of Alg. 2's 6, in exchange for ~16-bit instead of 8-bit weights.
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+
 template <bool SPLIT>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const __hip_bfloat16* __restrict__ V,
@@ -102,13 +100,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     float* __restrict__ O, float* __restrict__ tO, float* __restrict__ LSE,
     int Lq, int Lkv, float scale, int q_tiles) {
     extern __shared__ __attribute__((aligned(1024))) char smem[];
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(lds_char*)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c = lane & 31;          // query column of this lane in every MFMA result
-    const int g = lane >> 5;          // which half of the contraction index this lane feeds
-
+    const int c = lane & 31, g = lane >> 5;
     const int bid = blockIdx.x;
     const long bh = bid / q_tiles;
     const int q0 = (bid % q_tiles) * BR + wave * 32;
@@ -117,16 +113,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const char* tKh = reinterpret_cast<const char*>(tK) + bh * (long)Lkv * ROW_BYTES;
     const char* Vh = reinterpret_cast<const char*>(V) + bh * (long)Lkv * ROW_BYTES;
     const char* tVh = reinterpret_cast<const char*>(tV) + bh * (long)Lkv * ROW_BYTES;
+    const int n_blocks = (Lkv + BC - 1) / BC;
 
-    const int n_tiles = (Lkv + BC - 1) / BC;
+    issue_block_load(Kh, tKh, Vh, tVh, 0, Lkv, lds0, wave, lane);
+    issue_block_load(Kh, tKh, Vh, tVh, BC, Lkv, lds0 + STAGE_BYTES, wave, lane);
 
-    // prefetch tile 0 while Q is being fetched
-    issue_tile_load<false>(Kh, 0, Lkv, lds0 + 0 * TILE_BYTES, wave, lane);
-    issue_tile_load<false>(tKh, 0, Lkv, lds0 + 1 * TILE_BYTES, wave, lane);
-    issue_tile_load<true>(Vh, 0, Lkv, lds0 + 2 * TILE_BYTES, wave, lane);
-    issue_tile_load<true>(tVh, 0, Lkv, lds0 + 3 * TILE_BYTES, wave, lane);
-
-    // Q^T / tQ^T as MFMA B operand: lane (c, g) holds row q0+c, elements 16t + 8g .. +7
     const int qrow = q0 + c;
     const int qrow_ld = qrow < Lq ? qrow : Lq - 1;
     bf16x8 qf[8], tqf[8];
@@ -134,22 +125,19 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         const bf16x8* qp = reinterpret_cast<const bf16x8*>(Q + (bh * Lq + qrow_ld) * D + 8 * g);
         const bf16x8* tqp = reinterpret_cast<const bf16x8*>(tQ + (bh * Lq + qrow_ld) * D + 8 * g);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            qf[t] = qp[2 * t];
-            tqf[t] = tqp[2 * t];
-        }
+        for (int t = 0; t < 8; ++t) { qf[t] = qp[2 * t]; tqf[t] = tqp[2 * t]; }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) { asm volatile("" : "+a"(qf[t])); asm volatile("" : "+a"(tqf[t])); }
     }
 
-    // per-lane LDS read offsets (relative to a tensor's tile base)
-    uint32_t kaddr[8];
+    uint32_t kaddr0[8], vaddr0[4];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) kaddr[t] = c * ROW_BYTES + (((2 * t + g) ^ (c & 15)) << 4);
-    uint32_t vaddr[4];
+    for (int t = 0; t < 8; ++t) kaddr0[t] = lds0 + c * ROW_BYTES + (((2 * t + g) ^ (c & 15)) << 4);
     {
         const int i = lane & 15, hb = (lane >> 4) & 1;
         const uint32_t rowpart = (4 * g + (i >> 2)) * ROW_BYTES + (2 * hb + ((i & 3) >> 1)) * 16 + 8 * (i & 1);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) vaddr[db] = rowpart + ((db ^ (i >> 2)) << 6);
+        for (int db = 0; db < 4; ++db) vaddr0[db] = lds0 + rowpart + ((db ^ (i >> 2)) << 6);
     }
 
     f32x16 accO[4], accAB[4];
@@ -159,78 +147,267 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
 
     const float c2 = scale * 1.4426950408889634f;   // scores -> base-2 exponent
-    float m = -INFINITY;      // running max of c2 * s_raw, identical in lanes l and l^32
-    float l_part = 0.f;       // this lane's share of the row sum of P~
-    float r_part = 0.f;       // this lane's share of the row sum of H~ = P~ o (tS - ctr)
-    float ctr = 0.f;          // per-row constant subtracted from tS before H~ is rounded to bf16
+    float m, ctr;             // per-row exponent reference and tangent-score centre, fixed for the fast sweep
+    float l_part, r_part;     // this lane's share of rowsum(P~) and of rowsum(H~), H~ = P~ o (tS - ctr)
 
-    for (int j = 0; j < n_tiles; ++j) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // tile j is in LDS for every wave; every wave is done with the other stage
-        if (j + 1 < n_tiles) {
-            const uint32_t nb = lds0 + ((j + 1) & 1) * STAGE_BYTES;
-            const int j0n = (j + 1) * BC;
-            issue_tile_load<false>(Kh, j0n, Lkv, nb + 0 * TILE_BYTES, wave, lane);
-            issue_tile_load<false>(tKh, j0n, Lkv, nb + 1 * TILE_BYTES, wave, lane);
-            issue_tile_load<true>(Vh, j0n, Lkv, nb + 2 * TILE_BYTES, wave, lane);
-            issue_tile_load<true>(tVh, j0n, Lkv, nb + 3 * TILE_BYTES, wave, lane);
+    uint32_t wp[8], wh[8];
+    uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT ? 8 : 1];
+
+    // softmax arithmetic of one pair of score elements (e, e+1) -> packed weights
+    auto softmax_pair = [&](auto E, const float (&sv)[16], const float (&tsv)[16]) __attribute__((always_inline)) {
+        constexpr int e = decltype(E)::value;
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
+        const float h0 = p0 * fmaf(tsv[e], scale, -ctr);
+        const float h1 = p1 * fmaf(tsv[e + 1], scale, -ctr);
+        l_part += p0 + p1;
+        r_part += h0 + h1;
+        const uint32_t ph = pack_bf16(p0, p1);
+        const uint32_t hh = pack_bf16(h0, h1);
+        wp[e >> 1] = ph;
+        wh[e >> 1] = hh;
+        if constexpr (SPLIT) {   // lo = x - hi (exact in fp32), rounded to bf16
+            wpl[e >> 1] = pack_bf16(p0 - __uint_as_float(ph << 16), p1 - __uint_as_float(ph & 0xffff0000u));
+            whl[e >> 1] = pack_bf16(h0 - __uint_as_float(hh << 16), h1 - __uint_as_float(hh & 0xffff0000u));
         }
-        const uint32_t sb = lds0 + (j & 1) * STAGE_BYTES;
-        const bool tail = (j + 1) * BC > Lkv;
+    };
 
+    float sv[16], tsv[16];    // scores of the block whose softmax comes next, in ordinary registers
+    auto mask_scores = [&](int blk) __attribute__((always_inline)) {   // keys past Lkv: P~ = 0, tangent score 0
+        const int jbase = blk * BC + 4 * g;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            // ---- scores: S^T, tS^T for 32 keys x 32 queries
-            f32x16 s, ts;
+        for (int e = 0; e < 16; ++e) {
+            const int jj = jbase + 8 * (e >> 2) + (e & 3);
+            if (jj >= Lkv) { sv[e] = -INFINITY; tsv[e] = 0.f; }
+        }
+    };
+    auto plain_scores = [&](uint32_t stage_off) __attribute__((always_inline)) {
+        f32x16 s, ts;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                const bf16x8 kf = lds_read_b128(sb + 0 * TILE_BYTES + kb * 32 * ROW_BYTES + kaddr[t]);
-                const bf16x8 tkf = lds_read_b128(sb + 1 * TILE_BYTES + kb * 32 * ROW_BYTES + kaddr[t]);
-                s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[t], s, 0, 0, 0);
-                ts = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, tqf[t], ts, 0, 0, 0);
-                ts = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tkf, qf[t], ts, 0, 0, 0);
-            }
-            if (tail) {   // keys past Lkv: score -inf (P~ = 0), tangent score 0
-                const int jbase = j * BC + kb * 32 + 4 * g;
+        for (int t = 0; t < 8; ++t) {
+            const bf16x8 kf = lds_read_b128(kaddr0[t] + stage_off + OFF_K);
+            const bf16x8 tkf = lds_read_b128(kaddr0[t] + stage_off + OFF_TK);
+            s = MFMA(kf, qf[t], s);
+            ts = MFMA(kf, tqf[t], ts);
+            ts = MFMA(tkf, qf[t], ts);
+        }
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int jj = jbase + 8 * (e >> 2) + (e & 3);
-                    if (jj >= Lkv) { s[e] = -INFINITY; ts[e] = 0.f; }
+        for (int e = 0; e < 16; ++e) { sv[e] = s[e]; tsv[e] = ts[e]; }
+    };
+    auto row_max = [&]() __attribute__((always_inline)) -> float {
+        float t0 = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+        float t1 = fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7]));
+        float t2_ = fmaxf(fmaxf(sv[8], sv[9]), fmaxf(sv[10], sv[11]));
+        float t3 = fmaxf(fmaxf(sv[12], sv[13]), fmaxf(sv[14], sv[15]));
+        return xhalf_max(fmaxf(fmaxf(t0, t1), fmaxf(t2_, t3))) * c2;
+    };
+    auto plain_values = [&](uint32_t stage_off) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) {
+            const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
+            const bf16x8 hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const uint32_t a = vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
+                const bf16x8 vf = join_tr(lds_read_tr_b64(a + OFF_V), lds_read_tr_b64(a + OFF_V + 8 * ROW_BYTES));
+                const bf16x8 tvf = join_tr(lds_read_tr_b64(a + OFF_TV), lds_read_tr_b64(a + OFF_TV + 8 * ROW_BYTES));
+                accO[db] = MFMA(vf, pb, accO[db]);
+                accAB[db] = MFMA(tvf, pb, accAB[db]);
+                accAB[db] = MFMA(vf, hb8, accAB[db]);
+                if constexpr (SPLIT) {
+                    const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
+                    const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
+                    accO[db] = MFMA(vf, pl8, accO[db]);
+                    accAB[db] = MFMA(tvf, pl8, accAB[db]);
+                    accAB[db] = MFMA(vf, hl8, accAB[db]);
                 }
             }
-            // ---- online softmax (base 2) with re-centred tangent scores
-            float tmax = s[0];
+        }
+    };
+
+    // ================================ fast sweep ================================
+    // Alg. 2 with the running maximum replaced by a per-row exponent reference fixed after block 0:
+    // m = (block-0 maximum) + REF_HEADROOM.  exp2(S c2 - m) stays representable while later scores exceed
+    // the block-0 maximum by less than ~100 binades, which the sweep verifies at its end (see the check
+    // below); Alg. 2's rescale factors are then all exp(0) = 1 and no accumulator is ever rewritten.
+    // ctr is fixed to block 0's value of rowsum(P o tS).  The loop body is one straight-line region.
+    constexpr float REF_HEADROOM = 40.f;   // binades left above the block-0 maximum
+    float headroom = REF_HEADROOM;
+    {
+        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");   // block 0 landed (block 1 and Q may be in flight)
+        __syncthreads();
+        issue_block_load(Kh, tKh, Vh, tVh, 2 * BC, Lkv, lds0 + 2 * STAGE_BYTES, wave, lane);
+        plain_scores(0);
+        if (n_blocks == 1) mask_scores(0);
+        m = row_max() + REF_HEADROOM;
+        float lb = 0.f, rb = 0.f;
 #pragma unroll
-            for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, s[e]);
-            tmax = xhalf_max(tmax) * c2;
-            const bool raise = __builtin_amdgcn_ballot_w64(tmax > m) != 0;   // wave-uniform
-            float alpha = 1.f;
-            if (raise) {
-                const float m_new = fmaxf(m, tmax);
-                alpha = __builtin_amdgcn_exp2f(m - m_new);   // exp2(-inf) = 0 on the first block
-                m = m_new;
+        for (int e = 0; e < 16; ++e) {
+            const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
+            lb += pe;
+            rb = fmaf(pe, tsv[e] * scale, rb);
+        }
+        ctr = xhalf_sum(rb) / xhalf_sum(lb);
+        l_part = 0.f;
+        r_part = 0.f;
+    }
+
+    // Iteration b: [S(b+1) MFMAs || softmax(b)] [PV(b) MFMAs || fetch of block b+1's scores].
+    // The score MFMAs of a block past the end are harmless (the ring stage holds clamped duplicate rows).
+    auto iteration = [&](int b) __attribute__((always_inline)) {
+        const uint32_t k_off = (uint32_t)((b + 1) & 3) * STAGE_BYTES;
+        const uint32_t v_off = (uint32_t)(b & 3) * STAGE_BYTES;
+
+#ifndef EXP_NO_SYNC
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // all but the newest block load (block b+2) have landed
+        __syncthreads();   // block b+1 visible to all waves; all waves are done with block b-1's stage
+#endif
+        FENCE();
+        uint32_t ka[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) ka[t] = kaddr0[t] + k_off;
+        bf16x8 kf[3], tkf[3];
+        kf[0] = lds_read_b128(ka[0] + OFF_K);
+        kf[1] = lds_read_b128(ka[1] + OFF_K);
+        kf[2] = lds_read_b128(ka[2] + OFF_K);
+        FENCE();
+#ifndef EXP_NO_LOAD
+        issue_block_load(Kh, tKh, Vh, tVh, (b + 3) * BC, Lkv, lds0 + (uint32_t)((b + 3) & 3) * STAGE_BYTES, wave, lane);
+#endif
+        FENCE();
+        uint32_t va[4];
+#pragma unroll
+        for (int db = 0; db < 4; ++db) va[db] = vaddr0[db] + v_off;
+        FENCE();
+
+        // ---- phase 1: 24 score MFMAs of block b+1, softmax(b) underneath (one pair of elements per 2 MFMAs)
+        f32x16 s, ts;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
+        bf16x8 vf[2], tvf[2];
+        static_for<8>([&](auto T) {
+            constexpr int t = decltype(T)::value;
+            s = MFMA(kf[t % 3], qf[t], s);
+#ifndef EXP_NO_SOFTMAX
+            softmax_pair(std::integral_constant<int, 2 * t>{}, sv, tsv);
+#endif
+            FENCE();
+            ts = MFMA(kf[t % 3], tqf[t], ts);
+            if (t < 3) tkf[t] = lds_read_b128(ka[t] + OFF_TK);
+            FENCE();
+            if (t + 3 < 8) kf[t % 3] = lds_read_b128(ka[t + 3] + OFF_K);
+            FENCE();
+        });
+        static_for<8>([&](auto T) {
+            constexpr int t = decltype(T)::value;
+            ts = MFMA(tkf[t % 3], qf[t], ts);
+            FENCE();
+            if (t + 3 < 8) tkf[t % 3] = lds_read_b128(ka[t + 3] + OFF_TK);
+            if (t == 5) {
+                vf[0] = join_tr(lds_read_tr_b64(va[0] + OFF_V), lds_read_tr_b64(va[0] + OFF_V + 8 * ROW_BYTES));
+                tvf[0] = join_tr(lds_read_tr_b64(va[0] + OFF_TV), lds_read_tr_b64(va[0] + OFF_TV + 8 * ROW_BYTES));
             }
-            float p[16];
+            FENCE();
+        });
+
+        // ---- phase 2: value MFMAs of block b, fetch of block b+1's scores underneath
+        static_for<8>([&](auto Gc) {
+            constexpr int gi = decltype(Gc)::value;     // group = (t2, db)
+            constexpr int t2 = gi >> 2, db = gi & 3;
+            constexpr int cur = gi & 1, nxt = cur ^ 1;
+            const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
+            const bf16x8 hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
+            if (gi + 1 < 8) {
+                constexpr int t2n = (gi + 1) >> 2, dbn = (gi + 1) & 3;
+                const uint32_t a = va[dbn] + t2n * 16 * ROW_BYTES;
+                vf[nxt] = join_tr(lds_read_tr_b64(a + OFF_V), lds_read_tr_b64(a + OFF_V + 8 * ROW_BYTES));
+                tvf[nxt] = join_tr(lds_read_tr_b64(a + OFF_TV), lds_read_tr_b64(a + OFF_TV + 8 * ROW_BYTES));
+            }
+            accO[db] = MFMA(vf[cur], pb, accO[db]);
+            if (gi >= 2) {   // the score MFMAs have drained by now
+                sv[2 * (gi - 2)] = s[2 * (gi - 2)];
+                sv[2 * (gi - 2) + 1] = s[2 * (gi - 2) + 1];
+                tsv[2 * (gi - 2)] = ts[2 * (gi - 2)];
+                tsv[2 * (gi - 2) + 1] = ts[2 * (gi - 2) + 1];
+            }
+            FENCE();
+            accAB[db] = MFMA(tvf[cur], pb, accAB[db]);
+            if (gi == 7) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) p[e] = __builtin_amdgcn_exp2f(fmaf(s[e], c2, -m));
-            if (raise) {
-                // Some row's maximum moved, so every accumulator is touched anyway: use the pass to move the
-                // centring constant ctr of ALL 32 rows to the current estimate of mu = rowsum(P o tS) (this block
-                // included, taken before H~ is rounded).  Exact in real arithmetic for any ctr:
-                //   sum_j P~_j (tS_j - ctr_new) V_j = sum_j P~_j (tS_j - ctr_old) V_j - (ctr_new - ctr_old) O~.
+                for (int e = 12; e < 16; ++e) { sv[e] = s[e]; tsv[e] = ts[e]; }
+            }
+            FENCE();
+            accAB[db] = MFMA(vf[cur], hb8, accAB[db]);
+            if constexpr (SPLIT) {
+                const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
+                const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
+                FENCE();
+                accO[db] = MFMA(vf[cur], pl8, accO[db]);
+                FENCE();
+                accAB[db] = MFMA(tvf[cur], pl8, accAB[db]);
+                FENCE();
+                accAB[db] = MFMA(vf[cur], hl8, accAB[db]);
+            }
+            FENCE();
+        });
+    };
+
+    {
+        int b = 0;
+        for (; b + 2 < n_blocks; ++b) iteration(b);                    // fetched block b+1 <= n-2: full
+        if (b + 2 == n_blocks) { iteration(b); mask_scores(b + 1); ++b; }   // fetched block n-1: may be ragged
+        iteration(b);                                                    // b = n-1; fetched scores unused
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+
+    // Did the fixed exponent reference hold?  Row sums beyond 2^60 (or not finite) mean some score exceeded the
+    // block-0 maximum by ~100 binades.  Then the WHOLE workgroup redoes its tile with Alg. 2's running maximum.
+    {
+        const float l_chk = xhalf_sum(l_part), r_chk = xhalf_sum(r_part);
+        const bool bad = !(l_chk < 0x1p60f) || !(fabsf(r_chk) < 0x1p100f);
+        __syncthreads();                       // everyone is done with the ring
+        volatile __attribute__((address_space(3))) int* flag =
+            (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds0;
+        if (threadIdx.x == 0) *flag = 0;
+        __syncthreads();
+        if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) *flag = 1;
+        __syncthreads();
+        const bool redo = *flag != 0;
+        __syncthreads();
+        if (__builtin_expect(redo, 0)) {
+            // ============================ safe sweep (rare) ============================
+            // Alg. 2 as printed: per block, running maximum, rescale of every accumulator, no overlap.
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
+            m = -INFINITY; l_part = 0.f; r_part = 0.f; ctr = 0.f; headroom = 0.f;
+            issue_block_load(Kh, tKh, Vh, tVh, 0, Lkv, lds0, wave, lane);
+            for (int b = 0; b < n_blocks; ++b) {
+                const uint32_t off = (uint32_t)(b & 1) * STAGE_BYTES;
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+                issue_block_load(Kh, tKh, Vh, tVh, (b + 1) * BC, Lkv, lds0 + (uint32_t)((b + 1) & 1) * STAGE_BYTES, wave, lane);
+                plain_scores(off);
+                if ((b + 1) * BC > Lkv) mask_scores(b);
+                const float tmax = row_max();
+                const float m_new = fmaxf(m, tmax);
+                const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+                m = m_new;
                 float lb = 0.f, rb = 0.f;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                    lb += p[e];
-                    rb = fmaf(p[e], fmaf(ts[e], scale, -ctr), rb);
+                    const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
+                    lb += pe;
+                    rb = fmaf(pe, fmaf(tsv[e], scale, -ctr), rb);
                 }
                 l_part *= alpha;
                 r_part *= alpha;
                 const float l_row = xhalf_sum(l_part + lb);
                 const float r_row = xhalf_sum(r_part + rb);
-                const float delta = r_row / l_row;          // mu estimate minus ctr
+                const float delta = r_row / l_row;          // running rowsum(P o tS) minus ctr
                 ctr += delta;
                 r_part = fmaf(-delta, l_part, r_part);
                 const float da = delta * alpha;
@@ -241,66 +418,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                         accAB[db][e] = fmaf(accAB[db][e], alpha, -da * accO[db][e]);
                         accO[db][e] *= alpha;
                     }
+                static_for<8>([&](auto P) { softmax_pair(std::integral_constant<int, 2 * decltype(P)::value>{}, sv, tsv); });
+                plain_values(off);
             }
-            uint32_t pp[8], pq[8], hp[8], hq[8];   // P~^T, H~^T (hi, lo) as packed bf16 pairs, in result-register order
-#pragma unroll
-            for (int e = 0; e < 16; e += 2) {
-                const float h0 = p[e] * fmaf(ts[e], scale, -ctr);
-                const float h1 = p[e + 1] * fmaf(ts[e + 1], scale, -ctr);
-                l_part += p[e] + p[e + 1];
-                r_part += h0 + h1;
-                if (SPLIT) {
-                    // hi = x rounded to bf16, lo = x - hi (exact in fp32) rounded to bf16
-                    const uint32_t ph = pack_bf16(p[e], p[e + 1]);
-                    pp[e >> 1] = ph;
-                    pq[e >> 1] = pack_bf16(p[e] - __uint_as_float(ph << 16), p[e + 1] - __uint_as_float(ph & 0xffff0000u));
-                    const uint32_t hh = pack_bf16(h0, h1);
-                    hp[e >> 1] = hh;
-                    hq[e >> 1] = pack_bf16(h0 - __uint_as_float(hh << 16), h1 - __uint_as_float(hh & 0xffff0000u));
-                } else {
-                    pp[e >> 1] = pack_bf16(p[e], p[e + 1]);
-                    hp[e >> 1] = pack_bf16(h0, h1);
-                }
-            }
-            // ---- value contractions
-#pragma unroll
-            for (int t2 = 0; t2 < 2; ++t2) {
-                u32x4 pu = {pp[4 * t2], pp[4 * t2 + 1], pp[4 * t2 + 2], pp[4 * t2 + 3]};
-                u32x4 hu = {hp[4 * t2], hp[4 * t2 + 1], hp[4 * t2 + 2], hp[4 * t2 + 3]};
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, pu);
-                const bf16x8 hb8 = __builtin_bit_cast(bf16x8, hu);
-                bf16x8 hl8 = hb8, pl8 = pb;
-                if (SPLIT) {
-                    u32x4 lu = {hq[4 * t2], hq[4 * t2 + 1], hq[4 * t2 + 2], hq[4 * t2 + 3]};
-                    hl8 = __builtin_bit_cast(bf16x8, lu);
-                    u32x4 ql = {pq[4 * t2], pq[4 * t2 + 1], pq[4 * t2 + 2], pq[4 * t2 + 3]};
-                    pl8 = __builtin_bit_cast(bf16x8, ql);
-                }
-                const uint32_t rb = sb + (kb * 32 + t2 * 16) * ROW_BYTES;
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    const s16x4 v0 = lds_read_tr_b64(rb + 2 * TILE_BYTES + vaddr[db]);
-                    const s16x4 v1 = lds_read_tr_b64(rb + 2 * TILE_BYTES + 8 * ROW_BYTES + vaddr[db]);
-                    const s16x4 w0 = lds_read_tr_b64(rb + 3 * TILE_BYTES + vaddr[db]);
-                    const s16x4 w1 = lds_read_tr_b64(rb + 3 * TILE_BYTES + 8 * ROW_BYTES + vaddr[db]);
-                    typedef __attribute__((ext_vector_type(8))) short s16x8;
-                    const s16x8 vv = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    const s16x8 ww = __builtin_shufflevector(w0, w1, 0, 1, 2, 3, 4, 5, 6, 7);
-                    const bf16x8 vf = __builtin_bit_cast(bf16x8, vv);
-                    const bf16x8 tvf = __builtin_bit_cast(bf16x8, ww);
-                    accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pb, accO[db], 0, 0, 0);
-                    accAB[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tvf, pb, accAB[db], 0, 0, 0);
-                    accAB[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, hb8, accAB[db], 0, 0, 0);
-                    if (SPLIT) {
-                        accO[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pl8, accO[db], 0, 0, 0);
-                        accAB[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, hl8, accAB[db], 0, 0, 0);
-                    }
-                }
-            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
 
-    // ---- epilogue: O = O~/l, lse = m + log l, tO = (A + B - (r/l) O~) / l  (r and B both relative to ctr)
     const float l_row = xhalf_sum(l_part);
     const float r_row = xhalf_sum(r_part);
     const float inv_l = 1.f / l_row;
@@ -322,15 +446,15 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 *reinterpret_cast<float4*>(Op + 32 * db + 8 * v4) = o4;
                 *reinterpret_cast<float4*>(tOp + 32 * db + 8 * v4) = t4;
             }
-        if (g == 0) LSE[bh * Lq + qrow] = (m + __builtin_amdgcn_logf(l_row)) * 0.6931471805599453f;
+        // m carries `headroom` binades that l_row lacks: take them out of both before adding (exact scalings)
+        if (g == 0)
+            LSE[bh * Lq + qrow] = ((m - headroom) + __builtin_amdgcn_logf(l_row * __builtin_amdgcn_exp2f(headroom))) * 0.6931471805599453f;
     }
 }
 
 }  // namespace
 
-bool mfma_bf16_supports(const Problem& p) {
-    return p.in_dtype == 0 && p.out_dtype == 0 && p.d == D;
-}
+bool mfma_bf16_supports(const Problem& p) { return p.in_dtype == 0 && p.out_dtype == 0 && p.d == D; }
 
 hipError_t launch_mfma_bf16(const Problem& p) {
     if (!mfma_bf16_supports(p)) return hipErrorInvalidValue;

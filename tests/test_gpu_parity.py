@@ -91,8 +91,8 @@ def test_mfma_kernel_shapes(Lq, Lkv):
 
 # The FAST variant rounds P~ and H~ to single bf16 terms (relative rounding error up to 2^-8 per weight).  Its
 # error is heavy-tailed on rows where a handful of keys carry the weight (one product P~ (tS - ctr) V can
-# dominate), so it is held to a looser envelope than the default variant: 1.5e-2 of RMS(O), 6e-2 of RMS(tO).
-FAST_TOL = (1.5e-2, 6e-2, 1e-3)
+# dominate), so it is held to a looser envelope than the default variant: 2.5e-2 of RMS(O), 6e-2 of RMS(tO).
+FAST_TOL = (2.5e-2, 6e-2, 1e-3)
 
 
 @pytest.mark.parametrize("Lq,Lkv", [(1, 1), (128, 65), (200, 333), (517, 4), (384, 640)])
@@ -108,7 +108,7 @@ def test_mfma_fast_variant_config3_sample():
     got = run_gpu(t, cfg.scale, binding.KERNEL_MFMA, binding.FLAG_FAST)
     rows = sample_rows(cfg, 256)
     ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], cfg.scale, rows=rows)
-    compare(got, ref, cfg.torch_dtype, "cfg3 head 7 fast", rows=rows, tol=(1.5e-2, 2e-2, 1e-3))
+    compare(got, ref, cfg.torch_dtype, "cfg3 head 7 fast", rows=rows, tol=FAST_TOL)
 
 
 def test_mfma_default_entry_point_and_preallocated_outputs():
@@ -143,7 +143,7 @@ def test_mfma_structured_tangents():
     o, to, _ = run_gpu(t1, scale, binding.KERNEL_MFMA, binding.FLAG_FAST)
     np.testing.assert_array_equal(to, o)
     o, to, _ = run_gpu(t1, scale, binding.KERNEL_MFMA)
-    assert rel_err(to, o) <= 1e-2
+    assert rel_err(to, o) <= 1e-4
     # every key gets the same tangent vector u (tQ = tV = 0): tS is constant along each row, so tO = 0;
     # the kernel reaches it by cancelling B against r*O, which stresses the bf16 rounding of H~
     u = torch.randn(d, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
