@@ -1,4 +1,35 @@
-// v2 experiment: manual software pipeline with scheduling fences (vgpr-form MFMA).
+// bf16 matrix-core (MFMA) streaming kernel for attention forward + JVP (paper Alg. 2), d = 128.
+//
+// One workgroup = 4 wavefronts = 128 query rows; each wavefront owns 32 query rows for the whole
+// key/value sweep.  All contractions of Alg. 2's inner loop run on v_mfma_f32_32x32x16_bf16 in the
+// TRANSPOSED orientation: S^T = K Q^T, tS^T = K tQ^T + tK Q^T, O^T += V^T P~^T,
+// (A+B)^T += tV^T P~^T + V^T H~^T.  In that orientation a lane's MFMA result registers all belong
+// to ONE query (column = lane % 32), so
+//   * row max / row sums are in-lane reductions plus one exchange between lane l and l^32,
+//   * any per-row factor is a per-lane scalar,
+//   * P~^T and H~^T feed the next MFMA as its B operand straight from registers (the contraction
+//     index - the key position - may be enumerated in any order as long as both operands agree,
+//     and V^T is fetched from LDS in exactly the order the result registers happen to hold).
+// A and B of Alg. 2 share one accumulator: they carry the same rescale factor and are only added.
+//
+// Key/value blocks (32 rows x 128 bf16 per tensor) are copied HBM -> LDS with 128-bit direct-to-LDS loads
+// into two rings of 4 stages each (K|tK: 16 KiB per stage, V|tV: 16 KiB per stage, 128 KiB in all), K four
+// blocks and V three blocks ahead of the block being accumulated, XOR-swizzled so that both the row-wise
+// 128-bit reads (K, tK as MFMA A operand) and the transposing 64-bit reads (V, tV) spread over all banks.
+// Q and tQ fragments stay in registers (in the AGPR half of the file: only MFMA instructions read them).
+//
+// Software pipeline inside a wavefront (there is one wavefront per SIMD, so matrix and vector work
+// overlap only through the order of issue, fixed here by scheduling fences): the score MFMAs of block
+// b+1 run over block b's softmax arithmetic, the value MFMAs of block b over the fetch of block b+1's
+// scores from the accumulation registers; LDS fragments are requested several MFMAs ahead of their use.
+//
+// Numerics: bf16 operands, fp32 accumulation; softmax in base 2 with scale*log2(e) folded into one FMA.
+// The fast sweep fixes the exponent reference m per row after the first block (all of Alg. 2's rescale
+// factors become 1, so the accumulators are only ever written by MFMAs), checks at the end that this was
+// safe, and otherwise redoes the tile with Alg. 2's running maximum.  H~ = P~ o tS is formed as
+// P~ o (tS - ctr) with a per-row constant ctr near rowsum(P o tS): tP does not change when a constant is
+// added to a row of tS, and a small |tS - ctr| on the keys that carry the weight keeps the rounding of H~
+// from surviving the B - r O cancellation.
 #include "launchers.h"
 #include <hip/hip_bf16.h>
 #include <stdint.h>
@@ -16,12 +47,14 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int D = 128, BR = 128, BC = 32, NSTAGE = 4, NTHREADS = 256;
 constexpr int ROW_BYTES = D * 2;
-constexpr int TENSOR_BYTES = BC * ROW_BYTES;
-constexpr int STAGE_BYTES = 4 * TENSOR_BYTES;
-constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
-constexpr int OFF_K = 0, OFF_TK = TENSOR_BYTES, OFF_V = 2 * TENSOR_BYTES, OFF_TV = 3 * TENSOR_BYTES;
+constexpr int TENSOR_BYTES = BC * ROW_BYTES;            // one tensor's block: 8 KiB
+constexpr int KV_STAGE_BYTES = 2 * TENSOR_BYTES;        // K|tK or V|tV
+constexpr int V_RING_BASE = NSTAGE * KV_STAGE_BYTES;    // K ring at [0, 64 KiB), V ring at [64 KiB, 128 KiB)
+constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
 
+// nothing may be scheduled across a fence: the instruction order between fences is the issue order
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
+#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
 
 template <int N, typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
@@ -48,7 +81,7 @@ __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t addr) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         reinterpret_cast<__attribute__((address_space(3))) s16x4*>((uintptr_t)addr));
 }
-__device__ __forceinline__ float xhalf_max(float x) {
+__device__ __forceinline__ float xhalf_max(float x) {   // max of lane l and lane l^32, in both
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
@@ -57,7 +90,9 @@ __device__ __forceinline__ float xhalf_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    bf16x2 v; v[0] = (__bf16)lo; v[1] = (__bf16)hi;
+    bf16x2 v;
+    v[0] = (__bf16)lo;
+    v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
 }
 __device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
@@ -68,8 +103,31 @@ __device__ __forceinline__ bf16x8 join_tr(s16x4 a, s16x4 b) {
     return __builtin_bit_cast(bf16x8, __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
-__device__ __forceinline__ void issue_block_load(const char* Kh, const char* tKh, const char* Vh, const char* tVh,
-                                                 int j0, int Lkv, uint32_t stage_base, int wave, int lane) {
+// 128-bit direct-to-LDS loads (64 lanes x 16 B land at lds_base + 16 * lane; M0 carries lds_base).  Written as
+// inline assembly on purpose: the compiler orders LDS reads it cannot prove disjoint behind EVERY outstanding
+// direct-to-LDS load it knows of (a full vmcnt(0) wait before each transposing read), which would serialise the
+// ring.  Here the kernel does its own accounting: these are the only vector-memory loads in flight during the
+// sweep, each wave issues them in program order, and explicit s_waitcnt vmcnt(N) + barriers publish a stage before
+// anyone reads it.  M0 is not used by anything else in this kernel.
+__device__ __forceinline__ void load_lds_b128(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_base), "v"(gptr) : "memory");
+}
+// same with a uniform 64-bit base (scalar registers) and a per-lane 32-bit byte offset
+__device__ __forceinline__ void load_lds_b128(const void* uniform_base, uint32_t lane_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(lds_base), "v"(lane_off), "s"(uniform_base) : "memory");
+}
+#define ATTN_JVP_LOAD_LDS(g, l) load_lds_b128((g), __builtin_amdgcn_readfirstlane(l))
+
+// Copy one 32-row block of a tensor pair (X, tX) into an LDS stage (X at stage_base, tX TENSOR_BYTES above).
+// Each direct-to-LDS instruction moves 64 x 16 B = 4 rows; the LDS side is linear in the lane id, so the swizzle is
+// applied by choosing which 16-byte chunk of the row each lane fetches: K, tK: chunk ^= row & 15 (row-wise b128
+// reads); V, tV (VSWZ): chunk ^= (row & 3) << 2 (transposing b64 reads).  Rows past Lkv re-read the last valid
+// row (finite values; their scores are masked to -inf).
+template <bool VSWZ>
+__device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* tXh, int j0, int Lkv,
+                                                   uint32_t stage_base, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int rowblk = wave * 2 + i;
@@ -77,22 +135,39 @@ __device__ __forceinline__ void issue_block_load(const char* Kh, const char* tKh
         const int pc = lane & 15;
         int grow = j0 + row;
         grow = grow < Lkv ? grow : Lkv - 1;
-        const long goff_k = (long)grow * ROW_BYTES + ((pc ^ (row & 15)) << 4);
-        const long goff_v = (long)grow * ROW_BYTES + ((pc ^ ((row & 3) << 2)) << 4);
+        const long goff = (long)grow * ROW_BYTES + ((VSWZ ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15))) << 4);
         const uint32_t dst = stage_base + rowblk * 1024;
-#define ATTN_JVP_LOAD_LDS(g, l)                                                                        \
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g),               \
-                                     (__attribute__((address_space(3))) void*)(uintptr_t)(l), 16, 0, 0)
-        ATTN_JVP_LOAD_LDS(Kh + goff_k, dst + OFF_K);
-        ATTN_JVP_LOAD_LDS(tKh + goff_k, dst + OFF_TK);
-        ATTN_JVP_LOAD_LDS(Vh + goff_v, dst + OFF_V);
-        ATTN_JVP_LOAD_LDS(tVh + goff_v, dst + OFF_TV);
-#undef ATTN_JVP_LOAD_LDS
+        ATTN_JVP_LOAD_LDS(Xh + goff, dst);
+        ATTN_JVP_LOAD_LDS(tXh + goff, dst + TENSOR_BYTES);
+    }
+}
+// Same copy for a block known to lie entirely inside the sequence: the per-lane byte offsets (row and swizzled
+// chunk) never change, so they are computed once and only the uniform block base advances.
+struct LaneOffsets { uint32_t k[2], v[2]; };
+__device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane) {
+    LaneOffsets o;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int row = (wave * 2 + i) * 4 + (lane >> 4);
+        const int pc = lane & 15;
+        o.k[i] = row * ROW_BYTES + ((pc ^ (row & 15)) << 4);
+        o.v[i] = row * ROW_BYTES + ((pc ^ ((row & 3) << 2)) << 4);
+    }
+    return o;
+}
+__device__ __forceinline__ void issue_pair_full(const char* Xh, const char* tXh, int blk, const uint32_t (&lo)[2],
+                                                uint32_t stage_base, int wave) {
+    const long boff = (long)blk * (BC * ROW_BYTES);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t dst = stage_base + (wave * 2 + i) * 1024;
+        ATTN_JVP_LOAD_LDS(Xh + boff + lo[i], dst);
+        ATTN_JVP_LOAD_LDS(tXh + boff + lo[i], dst + TENSOR_BYTES);
     }
 }
 
-#define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
-
+// SPLIT: the weights P~ and H~ enter all three value contractions as hi + lo bf16 pairs: 9 matrix products per
+// key block instead of Alg. 2's 6, in exchange for ~16-bit instead of 8-bit weights.
 template <bool SPLIT>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const __hip_bfloat16* __restrict__ V,
@@ -104,7 +179,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int c = lane & 31, g = lane >> 5;
+    const int c = lane & 31;          // query column of this lane in every MFMA result
+    const int g = lane >> 5;          // which half of the contraction index this lane feeds
     const int bid = blockIdx.x;
     const long bh = bid / q_tiles;
     const int q0 = (bid % q_tiles) * BR + wave * 32;
@@ -115,9 +191,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const char* tVh = reinterpret_cast<const char*>(tV) + bh * (long)Lkv * ROW_BYTES;
     const int n_blocks = (Lkv + BC - 1) / BC;
 
-    issue_block_load(Kh, tKh, Vh, tVh, 0, Lkv, lds0, wave, lane);
-    issue_block_load(Kh, tKh, Vh, tVh, BC, Lkv, lds0 + STAGE_BYTES, wave, lane);
+    // block x: K|tK in K-ring stage x & 3, V|tV in V-ring stage x & 3
+    auto copy_k = [&](int blk) __attribute__((always_inline)) {
+        issue_pair_clamped<false>(Kh, tKh, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
+    };
+    auto copy_v = [&](int blk) __attribute__((always_inline)) {
+        issue_pair_clamped<true>(Vh, tVh, blk * BC, Lkv, lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES,
+                                 wave, lane);
+    };
+    // start the rings while Q is being fetched (rows past the end are clamped, so all copies are unconditional)
+    copy_k(0); copy_v(0); copy_k(1); copy_v(1); copy_k(2); copy_v(2); copy_k(3);
 
+    // Q^T / tQ^T as MFMA B operand: lane (c, g) holds row q0+c, elements 16t + 8g .. +7
     const int qrow = q0 + c;
     const int qrow_ld = qrow < Lq ? qrow : Lq - 1;
     bf16x8 qf[8], tqf[8];
@@ -127,9 +212,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #pragma unroll
         for (int t = 0; t < 8; ++t) { qf[t] = qp[2 * t]; tqf[t] = tqp[2 * t]; }
 #pragma unroll
-        for (int t = 0; t < 8; ++t) { asm volatile("" : "+a"(qf[t])); asm volatile("" : "+a"(tqf[t])); }
+        for (int t = 0; t < 8; ++t) {   // keep them in accumulation registers: only MFMAs read them
+            asm volatile("" : "+a"(qf[t]));
+            asm volatile("" : "+a"(tqf[t]));
+        }
     }
 
+    // per-lane LDS read addresses within stage 0 of the K ring / of the V ring; stage and tensor offsets are
+    // 16-bit immediates of the read instructions
     uint32_t kaddr0[8], vaddr0[4];
 #pragma unroll
     for (int t = 0; t < 8; ++t) kaddr0[t] = lds0 + c * ROW_BYTES + (((2 * t + g) ^ (c & 15)) << 4);
@@ -137,7 +227,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         const int i = lane & 15, hb = (lane >> 4) & 1;
         const uint32_t rowpart = (4 * g + (i >> 2)) * ROW_BYTES + (2 * hb + ((i & 3) >> 1)) * 16 + 8 * (i & 1);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) vaddr0[db] = lds0 + rowpart + ((db ^ (i >> 2)) << 6);
+        for (int db = 0; db < 4; ++db) vaddr0[db] = lds0 + V_RING_BASE + rowpart + ((db ^ (i >> 2)) << 6);
     }
 
     f32x16 accO[4], accAB[4];
@@ -150,29 +240,54 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     float m, ctr;             // per-row exponent reference and tangent-score centre, fixed for the fast sweep
     float l_part, r_part;     // this lane's share of rowsum(P~) and of rowsum(H~), H~ = P~ o (tS - ctr)
 
-    uint32_t wp[8], wh[8];
-    uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT ? 8 : 1];
+    uint32_t wp[8], wh[8];                              // P~^T, H~^T as packed bf16 pairs, result-register order
+    uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT ? 8 : 1];    // their low-order parts
 
-    // softmax arithmetic of one pair of score elements (e, e+1) -> packed weights
-    auto softmax_pair = [&](auto E, const float (&sv)[16], const float (&tsv)[16]) __attribute__((always_inline)) {
-        constexpr int e = decltype(E)::value;
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
-        const float h0 = p0 * fmaf(tsv[e], scale, -ctr);
-        const float h1 = p1 * fmaf(tsv[e + 1], scale, -ctr);
-        l_part += p0 + p1;
-        r_part += h0 + h1;
-        const uint32_t ph = pack_bf16(p0, p1);
-        const uint32_t hh = pack_bf16(h0, h1);
-        wp[e >> 1] = ph;
-        wh[e >> 1] = hh;
-        if constexpr (SPLIT) {   // lo = x - hi (exact in fp32), rounded to bf16
-            wpl[e >> 1] = pack_bf16(p0 - __uint_as_float(ph << 16), p1 - __uint_as_float(ph & 0xffff0000u));
-            whl[e >> 1] = pack_bf16(h0 - __uint_as_float(hh << 16), h1 - __uint_as_float(hh & 0xffff0000u));
+    float sv[16], tsv[16];    // scores of the block whose softmax comes next, in ordinary registers
+
+    // Softmax arithmetic of one pair of score elements (2j, 2j+1) -> packed weights, cut into five parts of at most
+    // six vector instructions so that the pipelined sweep can put one part behind each MFMA:
+    //   0: P~ = exp2(S c2 - m)   1: H~ = P~ (tS scale - ctr)   2: row sums   3: pack P~ (hi, lo)   4: pack H~ (hi, lo)
+    float sp0, sp1, sh0, sh1;
+    auto softmax_part = [&](auto J, auto PART) __attribute__((always_inline)) {
+        constexpr int j = decltype(J)::value, e = 2 * j, part = decltype(PART)::value;
+        if constexpr (part == 0) {
+            sp0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
+            sp1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
+        } else if constexpr (part == 1) {
+            sh0 = sp0 * fmaf(tsv[e], scale, -ctr);
+            sh1 = sp1 * fmaf(tsv[e + 1], scale, -ctr);
+        } else if constexpr (part == 2) {
+            l_part += sp0 + sp1;
+            r_part += sh0 + sh1;
+        } else if constexpr (part == 3) {
+            const uint32_t ph = pack_bf16(sp0, sp1);
+            wp[j] = ph;
+            if constexpr (SPLIT)   // lo = x - hi (exact in fp32), rounded to bf16
+                wpl[j] = pack_bf16(sp0 - __uint_as_float(ph << 16), sp1 - __uint_as_float(ph & 0xffff0000u));
+        } else if constexpr (part == 4) {
+            const uint32_t hh = pack_bf16(sh0, sh1);
+            wh[j] = hh;
+            if constexpr (SPLIT)
+                whl[j] = pack_bf16(sh0 - __uint_as_float(hh << 16), sh1 - __uint_as_float(hh & 0xffff0000u));
+        }
+    };
+    auto softmax_pair = [&](auto J) __attribute__((always_inline)) {
+        static_for<5>([&](auto PART) { softmax_part(J, PART); });
+    };
+    // the part that goes behind MFMA number `slot` of the `n_slots` (3 or 6) a pair has to itself
+    auto softmax_slot = [&](auto J, auto SLOT, auto NSLOTS) __attribute__((always_inline)) {
+        constexpr int slot = decltype(SLOT)::value, n_slots = decltype(NSLOTS)::value;
+        if constexpr (n_slots >= 5) {
+            if constexpr (slot < 5) softmax_part(J, SLOT);
+        } else {
+            static_assert(n_slots == 3, "a pair gets 3 or at least 5 MFMA slots");
+            if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{});
+            if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}); softmax_part(J, std::integral_constant<int, 3>{}); }
+            if constexpr (slot == 2) { softmax_part(J, std::integral_constant<int, 2>{}); softmax_part(J, std::integral_constant<int, 4>{}); }
         }
     };
 
-    float sv[16], tsv[16];    // scores of the block whose softmax comes next, in ordinary registers
     auto mask_scores = [&](int blk) __attribute__((always_inline)) {   // keys past Lkv: P~ = 0, tangent score 0
         const int jbase = blk * BC + 4 * g;
 #pragma unroll
@@ -181,14 +296,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             if (jj >= Lkv) { sv[e] = -INFINITY; tsv[e] = 0.f; }
         }
     };
-    auto plain_scores = [&](uint32_t stage_off) __attribute__((always_inline)) {
+    auto plain_scores = [&](uint32_t stage_off) __attribute__((always_inline)) {   // unscheduled: prologue, safe sweep
         f32x16 s, ts;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
-            const bf16x8 kf = lds_read_b128(kaddr0[t] + stage_off + OFF_K);
-            const bf16x8 tkf = lds_read_b128(kaddr0[t] + stage_off + OFF_TK);
+            const bf16x8 kf = lds_read_b128(kaddr0[t] + stage_off);
+            const bf16x8 tkf = lds_read_b128(kaddr0[t] + stage_off + TENSOR_BYTES);
             s = MFMA(kf, qf[t], s);
             ts = MFMA(kf, tqf[t], ts);
             ts = MFMA(tkf, qf[t], ts);
@@ -203,7 +318,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         float t3 = fmaxf(fmaxf(sv[12], sv[13]), fmaxf(sv[14], sv[15]));
         return xhalf_max(fmaxf(fmaxf(t0, t1), fmaxf(t2_, t3))) * c2;
     };
-    auto plain_values = [&](uint32_t stage_off) __attribute__((always_inline)) {
+    auto plain_values = [&](uint32_t stage_off) __attribute__((always_inline)) {   // unscheduled: safe sweep
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
             const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
@@ -211,8 +326,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
                 const uint32_t a = vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
-                const bf16x8 vf = join_tr(lds_read_tr_b64(a + OFF_V), lds_read_tr_b64(a + OFF_V + 8 * ROW_BYTES));
-                const bf16x8 tvf = join_tr(lds_read_tr_b64(a + OFF_TV), lds_read_tr_b64(a + OFF_TV + 8 * ROW_BYTES));
+                const bf16x8 vf = join_tr(lds_read_tr_b64(a), lds_read_tr_b64(a + 8 * ROW_BYTES));
+                const bf16x8 tvf = join_tr(lds_read_tr_b64(a + TENSOR_BYTES), lds_read_tr_b64(a + TENSOR_BYTES + 8 * ROW_BYTES));
                 accO[db] = MFMA(vf, pb, accO[db]);
                 accAB[db] = MFMA(tvf, pb, accAB[db]);
                 accAB[db] = MFMA(vf, hb8, accAB[db]);
@@ -232,13 +347,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // m = (block-0 maximum) + REF_HEADROOM.  exp2(S c2 - m) stays representable while later scores exceed
     // the block-0 maximum by less than ~100 binades, which the sweep verifies at its end (see the check
     // below); Alg. 2's rescale factors are then all exp(0) = 1 and no accumulator is ever rewritten.
-    // ctr is fixed to block 0's value of rowsum(P o tS).  The loop body is one straight-line region.
+    // ctr is fixed to block 0's value of rowsum(P o tS).  The loop body is straight-line code.
     constexpr float REF_HEADROOM = 40.f;   // binades left above the block-0 maximum
     float headroom = REF_HEADROOM;
     {
-        asm volatile("s_waitcnt vmcnt(24)" ::: "memory");   // block 0 landed (block 1 and Q may be in flight)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // K(0..3), V(0..2) and the Q fragments are in
         __syncthreads();
-        issue_block_load(Kh, tKh, Vh, tVh, 2 * BC, Lkv, lds0 + 2 * STAGE_BYTES, wave, lane);
         plain_scores(0);
         if (n_blocks == 1) mask_scores(0);
         m = row_max() + REF_HEADROOM;
@@ -252,113 +366,185 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         ctr = xhalf_sum(rb) / xhalf_sum(lb);
         l_part = 0.f;
         r_part = 0.f;
+        static_for<4>([&](auto J) { softmax_pair(J); });   // pairs 0-3 of block 0; pairs 4-7 follow in iteration 0
     }
 
-    // Iteration b: [S(b+1) MFMAs || softmax(b)] [PV(b) MFMAs || fetch of block b+1's scores].
-    // The score MFMAs of a block past the end are harmless (the ring stage holds clamped duplicate rows).
-    auto iteration = [&](int b) __attribute__((always_inline)) {
-        const uint32_t k_off = (uint32_t)((b + 1) & 3) * STAGE_BYTES;
-        const uint32_t v_off = (uint32_t)(b & 3) * STAGE_BYTES;
+    // ---- pipelined sweep.  Iteration b (U = b & 3 selects the ring stages at compile time):
+    //   phase 1: score MFMAs of block b+1, block b's softmax arithmetic underneath;
+    //   middle : wait for the copies issued two iterations ago, workgroup barrier, issue K(b+4) and V(b+3);
+    //   phase 2: value MFMAs of block b, fetch of block b+1's scores underneath.
+    // LDS fragments are requested well ahead of the MFMA that consumes them: the first KPRE score steps of the
+    // next iteration during phase 2, the first VPRE value groups during phase 1, the rest KPRE steps / VPRE
+    // groups ahead inside their own phase, through small register rings.
+    constexpr int KPRE = 3, KRING = KPRE + 1, VPRE = 2, VRING = VPRE + 1;
+    const LaneOffsets lofs = make_lane_offsets(wave, lane);
+    const int n_full = Lkv / BC;                       // blocks that need no row clamping
+    bf16x8 kfr[KRING], tkfr[KRING], vfr[VRING], tvfr[VRING];
+    auto read_k = [&](auto T, auto ST) __attribute__((always_inline)) {     // score step T of the block in K stage ST
+        constexpr int t = decltype(T)::value;
+        constexpr int off = decltype(ST)::value * KV_STAGE_BYTES;
+        kfr[t % KRING] = lds_read_b128(kaddr0[t] + off);
+        tkfr[t % KRING] = lds_read_b128(kaddr0[t] + off + TENSOR_BYTES);
+    };
+    auto read_v = [&](auto G, auto ST) __attribute__((always_inline)) {     // value group G of the block in V stage ST
+        constexpr int gi = decltype(G)::value;
+        constexpr int t2 = gi >> 2, db = gi & 3;
+        constexpr int off = decltype(ST)::value * KV_STAGE_BYTES + t2 * 16 * ROW_BYTES;
+        vfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off), lds_read_tr_b64(vaddr0[db] + off + 8 * ROW_BYTES));
+        tvfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES),
+                                   lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES + 8 * ROW_BYTES));
+    };
 
-#ifndef EXP_NO_SYNC
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // all but the newest block load (block b+2) have landed
-        __syncthreads();   // block b+1 visible to all waves; all waves are done with block b-1's stage
-#endif
-        FENCE();
-        uint32_t ka[8];
-#pragma unroll
-        for (int t = 0; t < 8; ++t) ka[t] = kaddr0[t] + k_off;
-        bf16x8 kf[3], tkf[3];
-        kf[0] = lds_read_b128(ka[0] + OFF_K);
-        kf[1] = lds_read_b128(ka[1] + OFF_K);
-        kf[2] = lds_read_b128(ka[2] + OFF_K);
-        FENCE();
-#ifndef EXP_NO_LOAD
-        issue_block_load(Kh, tKh, Vh, tVh, (b + 3) * BC, Lkv, lds0 + (uint32_t)((b + 3) & 3) * STAGE_BYTES, wave, lane);
-#endif
-        FENCE();
-        uint32_t va[4];
-#pragma unroll
-        for (int db = 0; db < 4; ++db) va[db] = vaddr0[db] + v_off;
-        FENCE();
+    // The copies of iteration b: K(b+4) into K stage b & 3, V(b+3) into V stage (b+3) & 3, as 8 direct-to-LDS
+    // instructions per wave.  They are issued ONE per value group in phase 2, not back to back: the vector memory
+    // pipe takes ~16 cycles per 1 KiB instruction and all four waves pass the barrier together, so a burst would
+    // stall the in-order instruction stream behind the queue.
+    auto issue_copy_piece = [&](auto FULLc, auto IDX, int b) __attribute__((always_inline)) {
+        constexpr int idx = decltype(IDX)::value;
+        constexpr int i = idx >> 2, which = idx & 3;      // row group of this wave; 0 K, 1 tK, 2 V, 3 tV
+        const int blk = which < 2 ? b + 4 : b + 3;
+        const char* base = which == 0 ? Kh : which == 1 ? tKh : which == 2 ? Vh : tVh;
+        const uint32_t dst = lds0 + (which < 2 ? 0 : V_RING_BASE) + (uint32_t)(blk & 3) * KV_STAGE_BYTES +
+                             (which & 1) * TENSOR_BYTES + (wave * 2 + i) * 1024;
+        if constexpr (decltype(FULLc)::value) {
+            const uint32_t lo = which < 2 ? lofs.k[i] : lofs.v[i];
+            load_lds_b128(base + (long)blk * (BC * ROW_BYTES), lo, __builtin_amdgcn_readfirstlane(dst));
+        } else {
+            const int row = (wave * 2 + i) * 4 + (lane >> 4);
+            const int pc = lane & 15;
+            int grow = blk * BC + row;
+            grow = grow < Lkv ? grow : Lkv - 1;
+            const int chunk = which < 2 ? (pc ^ (row & 15)) : (pc ^ ((row & 3) << 2));
+            ATTN_JVP_LOAD_LDS(base + (long)grow * ROW_BYTES + (chunk << 4), dst);
+        }
+    };
 
-        // ---- phase 1: 24 score MFMAs of block b+1, softmax(b) underneath (one pair of elements per 2 MFMAs)
+    // Vector work is spread so that no MFMA has more than ~6 vector instructions behind it (beyond that the single
+    // wavefront of a SIMD stops overlapping them with the matrix pipe):
+    //   phase 1 of iteration b  : weights of pairs 4-7 of block b   (scores fetched in phase 2 of iteration b-1)
+    //   phase 2, groups 0-3     : fetch of block b+1's scores (two pairs per group)
+    //   phase 2, groups 4-7     : weights of pairs 0-3 of block b+1 (their registers were consumed by groups 0-3)
+    auto iteration = [&](auto Uc, auto FULLc, int b) __attribute__((always_inline)) {
+        constexpr int U = decltype(Uc)::value;
+        constexpr bool FULL = decltype(FULLc)::value;
+        constexpr int GROUP_MFMAS = SPLIT ? 6 : 3;
+        using NS_P1 = std::integral_constant<int, 6>;             // phase 1: two score steps (6 MFMAs) per pair
+        using NS_P2 = std::integral_constant<int, GROUP_MFMAS>;   // phase 2: one value group per pair
+        using K1 = std::integral_constant<int, (U + 1) & 3>;    // K stage of block b+1
+        using K2 = std::integral_constant<int, (U + 2) & 3>;    // K stage of block b+2
+        using V0 = std::integral_constant<int, U>;              // V stage of block b
         f32x16 s, ts;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
-        bf16x8 vf[2], tvf[2];
+        // ---- phase 1
         static_for<8>([&](auto T) {
             constexpr int t = decltype(T)::value;
-            s = MFMA(kf[t % 3], qf[t], s);
+            using J = std::integral_constant<int, 4 + t / 2>;
+            constexpr int s0 = (t % 2) * 3;
+            s = MFMA(kfr[t % KRING], qf[t], s);
 #ifndef EXP_NO_SOFTMAX
-            softmax_pair(std::integral_constant<int, 2 * t>{}, sv, tsv);
+            softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{});
 #endif
             FENCE();
-            ts = MFMA(kf[t % 3], tqf[t], ts);
-            if (t < 3) tkf[t] = lds_read_b128(ka[t] + OFF_TK);
+            ts = MFMA(kfr[t % KRING], tqf[t], ts);
+#ifndef EXP_NO_SOFTMAX
+            softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{});
+#endif
             FENCE();
-            if (t + 3 < 8) kf[t % 3] = lds_read_b128(ka[t + 3] + OFF_K);
+            ts = MFMA(tkfr[t % KRING], qf[t], ts);
+#ifndef EXP_NO_SOFTMAX
+            softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{});
+#endif
             FENCE();
-        });
-        static_for<8>([&](auto T) {
-            constexpr int t = decltype(T)::value;
-            ts = MFMA(tkf[t % 3], qf[t], ts);
-            FENCE();
-            if (t + 3 < 8) tkf[t % 3] = lds_read_b128(ka[t + 3] + OFF_TK);
-            if (t == 5) {
-                vf[0] = join_tr(lds_read_tr_b64(va[0] + OFF_V), lds_read_tr_b64(va[0] + OFF_V + 8 * ROW_BYTES));
-                tvf[0] = join_tr(lds_read_tr_b64(va[0] + OFF_TV), lds_read_tr_b64(va[0] + OFF_TV + 8 * ROW_BYTES));
-            }
+            if constexpr (t + KPRE < 8) read_k(std::integral_constant<int, t + KPRE>{}, K1{});
+            if constexpr (t >= 8 - VPRE) read_v(std::integral_constant<int, t - (8 - VPRE)>{}, V0{});
             FENCE();
         });
-
-        // ---- phase 2: value MFMAs of block b, fetch of block b+1's scores underneath
+        // ---- middle
+#ifndef EXP_NO_SYNC
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // all but the newest copies landed: K(b+2), V(b+1) are in
+        __syncthreads();   // ... and visible to all waves; all waves are done with K(b) and V(b-1)
+#endif
+        FENCE();
+        // ---- phase 2
         static_for<8>([&](auto Gc) {
             constexpr int gi = decltype(Gc)::value;     // group = (t2, db)
             constexpr int t2 = gi >> 2, db = gi & 3;
-            constexpr int cur = gi & 1, nxt = cur ^ 1;
+            if constexpr (gi == 4 && !FULL) {
+                // tail iterations only: keys past Lkv (a ragged last block, or the unused block past the end)
+                if ((b + 2) * BC > Lkv) mask_scores(b + 1);
+            }
             const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
             const bf16x8 hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
-            if (gi + 1 < 8) {
-                constexpr int t2n = (gi + 1) >> 2, dbn = (gi + 1) & 3;
-                const uint32_t a = va[dbn] + t2n * 16 * ROW_BYTES;
-                vf[nxt] = join_tr(lds_read_tr_b64(a + OFF_V), lds_read_tr_b64(a + OFF_V + 8 * ROW_BYTES));
-                tvf[nxt] = join_tr(lds_read_tr_b64(a + OFF_TV), lds_read_tr_b64(a + OFF_TV + 8 * ROW_BYTES));
-            }
-            accO[db] = MFMA(vf[cur], pb, accO[db]);
-            if (gi >= 2) {   // the score MFMAs have drained by now
-                sv[2 * (gi - 2)] = s[2 * (gi - 2)];
-                sv[2 * (gi - 2) + 1] = s[2 * (gi - 2) + 1];
-                tsv[2 * (gi - 2)] = ts[2 * (gi - 2)];
-                tsv[2 * (gi - 2) + 1] = ts[2 * (gi - 2) + 1];
-            }
+            // vector work behind MFMA number `slot` of this group
+            auto behind = [&](auto SLOT) __attribute__((always_inline)) {
+                constexpr int slot = decltype(SLOT)::value;
+                if constexpr (gi < 4) {
+                    // scores of block b+1 out of the MFMA result registers: elements 4 gi .. 4 gi + 3
+                    if constexpr (slot == 0) { sv[4 * gi] = s[4 * gi]; sv[4 * gi + 1] = s[4 * gi + 1]; tsv[4 * gi] = ts[4 * gi]; tsv[4 * gi + 1] = ts[4 * gi + 1]; }
+                    if constexpr (slot == 1) { sv[4 * gi + 2] = s[4 * gi + 2]; sv[4 * gi + 3] = s[4 * gi + 3]; tsv[4 * gi + 2] = ts[4 * gi + 2]; tsv[4 * gi + 3] = ts[4 * gi + 3]; }
+                } else {
+#ifndef EXP_NO_SOFTMAX
+                    softmax_slot(std::integral_constant<int, gi - 4>{}, SLOT, NS_P2{});
+#endif
+                }
+            };
+            accO[db] = MFMA(vfr[gi % VRING], pb, accO[db]);
+            behind(std::integral_constant<int, 0>{});
             FENCE();
-            accAB[db] = MFMA(tvf[cur], pb, accAB[db]);
-            if (gi == 7) {
-#pragma unroll
-                for (int e = 12; e < 16; ++e) { sv[e] = s[e]; tsv[e] = ts[e]; }
-            }
+            accAB[db] = MFMA(tvfr[gi % VRING], pb, accAB[db]);
+            behind(std::integral_constant<int, 1>{});
             FENCE();
-            accAB[db] = MFMA(vf[cur], hb8, accAB[db]);
+            accAB[db] = MFMA(vfr[gi % VRING], hb8, accAB[db]);
+            behind(std::integral_constant<int, 2>{});
             if constexpr (SPLIT) {
                 const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                 const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
                 FENCE();
-                accO[db] = MFMA(vf[cur], pl8, accO[db]);
+                accO[db] = MFMA(vfr[gi % VRING], pl8, accO[db]);
+                behind(std::integral_constant<int, 3>{});
                 FENCE();
-                accAB[db] = MFMA(tvf[cur], pl8, accAB[db]);
+                accAB[db] = MFMA(tvfr[gi % VRING], pl8, accAB[db]);
+                behind(std::integral_constant<int, 4>{});
                 FENCE();
-                accAB[db] = MFMA(vf[cur], hl8, accAB[db]);
+                accAB[db] = MFMA(vfr[gi % VRING], hl8, accAB[db]);
             }
+            FENCE();
+#ifndef EXP_NO_LOAD
+            issue_copy_piece(FULLc, Gc, b);
+#endif
+            if constexpr (gi + VPRE < 8) read_v(std::integral_constant<int, gi + VPRE>{}, V0{});
+            if constexpr (gi >= 8 - KPRE) read_k(std::integral_constant<int, gi - (8 - KPRE)>{}, K2{});
             FENCE();
         });
     };
 
     {
+        static_for<KPRE>([&](auto T) { read_k(T, std::integral_constant<int, 1>{}); });   // K(1), landed in the prologue
+        FENCE();
+        using FY = std::integral_constant<bool, true>;
+        using FN = std::integral_constant<bool, false>;
+        using U0 = std::integral_constant<int, 0>;
+        using U1 = std::integral_constant<int, 1>;
+        using U2 = std::integral_constant<int, 2>;
+        using U3 = std::integral_constant<int, 3>;
         int b = 0;
-        for (; b + 2 < n_blocks; ++b) iteration(b);                    // fetched block b+1 <= n-2: full
-        if (b + 2 == n_blocks) { iteration(b); mask_scores(b + 1); ++b; }   // fetched block n-1: may be ragged
-        iteration(b);                                                    // b = n-1; fetched scores unused
+        // main loop: every block copied inside it (up to K(b+7)) is a full block
+        for (; b + 8 <= n_full; b += 4) {
+            iteration(U0{}, FY{}, b);
+            iteration(U1{}, FY{}, b + 1);
+            iteration(U2{}, FY{}, b + 2);
+            iteration(U3{}, FY{}, b + 3);
+        }
+        // tail: clamped copies, and masking of the keys past Lkv in the scores fetched for block b+1
+        for (; b < n_blocks; ++b) {
+            switch (b & 3) {
+                case 0: iteration(U0{}, FN{}, b); break;
+                case 1: iteration(U1{}, FN{}, b); break;
+                case 2: iteration(U2{}, FN{}, b); break;
+                default: iteration(U3{}, FN{}, b); break;
+            }
+        }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
@@ -367,7 +553,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     {
         const float l_chk = xhalf_sum(l_part), r_chk = xhalf_sum(r_part);
         const bool bad = !(l_chk < 0x1p60f) || !(fabsf(r_chk) < 0x1p100f);
-        __syncthreads();                       // everyone is done with the ring
+        __syncthreads();                       // everyone is done with the rings
         volatile __attribute__((address_space(3))) int* flag =
             (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds0;
         if (threadIdx.x == 0) *flag = 0;
@@ -379,17 +565,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         if (__builtin_expect(redo, 0)) {
             // ============================ safe sweep (rare) ============================
             // Alg. 2 as printed: per block, running maximum, rescale of every accumulator, no overlap.
+            // ctr follows the running value of rowsum(P o tS): B <- B - (ctr_new - ctr_old) O~ keeps it exact.
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
             m = -INFINITY; l_part = 0.f; r_part = 0.f; ctr = 0.f; headroom = 0.f;
-            issue_block_load(Kh, tKh, Vh, tVh, 0, Lkv, lds0, wave, lane);
+            copy_k(0); copy_v(0);
             for (int b = 0; b < n_blocks; ++b) {
-                const uint32_t off = (uint32_t)(b & 1) * STAGE_BYTES;
+                const uint32_t off = (uint32_t)(b & 3) * KV_STAGE_BYTES;
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
-                issue_block_load(Kh, tKh, Vh, tVh, (b + 1) * BC, Lkv, lds0 + (uint32_t)((b + 1) & 1) * STAGE_BYTES, wave, lane);
+                copy_k(b + 1); copy_v(b + 1);
                 plain_scores(off);
                 if ((b + 1) * BC > Lkv) mask_scores(b);
                 const float tmax = row_max();
@@ -418,13 +605,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                         accAB[db][e] = fmaf(accAB[db][e], alpha, -da * accO[db][e]);
                         accO[db][e] *= alpha;
                     }
-                static_for<8>([&](auto P) { softmax_pair(std::integral_constant<int, 2 * decltype(P)::value>{}, sv, tsv); });
+                static_for<8>([&](auto P) { softmax_pair(P); });
                 plain_values(off);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
 
+    // ---- epilogue: O = O~/l, lse = m + log l, tO = (A + B - (r/l) O~) / l  (r and B both relative to ctr)
     const float l_row = xhalf_sum(l_part);
     const float r_row = xhalf_sum(r_part);
     const float inv_l = 1.f / l_row;

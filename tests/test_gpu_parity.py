@@ -208,3 +208,13 @@ def test_config4_video_cross_all_rows():
 
 def test_config5_video_14b_stress():
     check_config_sampled(CONFIGS[5], 64)
+
+
+def test_mfma_safe_sweep_fallback():
+    """Keys after the first block carry scores ~100 nats above the first block's: the fast sweep's fixed exponent
+    reference cannot hold, the kernel must notice and redo the tile with the running maximum."""
+    t = random_inputs(41, 1, 2, 200, 300, 128, torch.bfloat16)
+    t["k"][:, :, 32:] *= 40.0
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback")
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, fast variant", flags=binding.FLAG_FAST,
+               tol=FAST_TOL)
