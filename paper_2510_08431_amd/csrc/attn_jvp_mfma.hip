@@ -67,7 +67,7 @@ __device__ __forceinline__ void static_for(F&& f) {
 
 __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
 #ifdef EXP_NO_LDS
-    u32x4 u = {addr, addr + 1, addr + 2, addr + 3};
+    u32x4 u = {0x3c003c00u + (addr & 1), 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
     return __builtin_bit_cast(bf16x8, u);
 #endif
     return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>((uintptr_t)addr);
@@ -75,7 +75,7 @@ __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
 __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t addr) {
 #ifdef EXP_NO_LDS
     typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_;
-    u32x2_ u = {addr, addr + 1};
+    u32x2_ u = {0x3c003c00u + (addr & 1), 0x3c003c00u};
     return __builtin_bit_cast(s16x4, u);
 #endif
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -377,6 +377,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // next iteration during phase 2, the first VPRE value groups during phase 1, the rest KPRE steps / VPRE
     // groups ahead inside their own phase, through small register rings.
     constexpr int KPRE = 3, KRING = KPRE + 1, VPRE = 2, VRING = VPRE + 1;
+    constexpr int KFIRST = 2;   // value group after which the next iteration's first score fragments are requested
     const LaneOffsets lofs = make_lane_offsets(wave, lane);
     const int n_full = Lkv / BC;                       // blocks that need no row clamping
     bf16x8 kfr[KRING], tkfr[KRING], vfr[VRING], tvfr[VRING];
@@ -463,7 +464,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         // ---- middle
 #ifndef EXP_NO_SYNC
         asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // all but the newest copies landed: K(b+2), V(b+1) are in
-        __syncthreads();   // ... and visible to all waves; all waves are done with K(b) and V(b-1)
+        // ... and visible to all waves after the barrier; all waves are done with K(b) and V(b-1).  A bare barrier:
+        // the LDS reads still in flight (first value fragments of block b) read stages nobody overwrites yet.
+        __builtin_amdgcn_s_barrier();
 #endif
         FENCE();
         // ---- phase 2
@@ -481,8 +484,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 constexpr int slot = decltype(SLOT)::value;
                 if constexpr (gi < 4) {
                     // scores of block b+1 out of the MFMA result registers: elements 4 gi .. 4 gi + 3
-                    if constexpr (slot == 0) { sv[4 * gi] = s[4 * gi]; sv[4 * gi + 1] = s[4 * gi + 1]; tsv[4 * gi] = ts[4 * gi]; tsv[4 * gi + 1] = ts[4 * gi + 1]; }
-                    if constexpr (slot == 1) { sv[4 * gi + 2] = s[4 * gi + 2]; sv[4 * gi + 3] = s[4 * gi + 3]; tsv[4 * gi + 2] = ts[4 * gi + 2]; tsv[4 * gi + 3] = ts[4 * gi + 3]; }
+                    // (the empty asm pins each copy to this point; otherwise the compiler sinks them all to their uses)
+                    if constexpr (slot == 1 || slot == 2) {
+                        constexpr int e0 = 4 * gi + 2 * (slot - 1);
+                        sv[e0] = s[e0]; sv[e0 + 1] = s[e0 + 1]; tsv[e0] = ts[e0]; tsv[e0 + 1] = ts[e0 + 1];
+                        asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]), "+v"(tsv[e0]), "+v"(tsv[e0 + 1]));
+                    }
                 } else {
 #ifndef EXP_NO_SOFTMAX
                     softmax_slot(std::integral_constant<int, gi - 4>{}, SLOT, NS_P2{});
@@ -514,7 +521,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             issue_copy_piece(FULLc, Gc, b);
 #endif
             if constexpr (gi + VPRE < 8) read_v(std::integral_constant<int, gi + VPRE>{}, V0{});
-            if constexpr (gi >= 8 - KPRE) read_k(std::integral_constant<int, gi - (8 - KPRE)>{}, K2{});
+            if constexpr (gi >= KFIRST && gi < KFIRST + KPRE) read_k(std::integral_constant<int, gi - KFIRST>{}, K2{});
             FENCE();
         });
     };
