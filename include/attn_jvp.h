@@ -15,7 +15,9 @@
  * multiplies both S and tS.
  *
  * Memory: every pointer is a DEVICE pointer owned by the caller; the library allocates
- * nothing, keeps no state between calls and needs no workspace.
+ * nothing and keeps no state between calls.  It needs no workspace; if the caller lends one
+ * (attn_jvp_opts.workspace, see attn_jvp_workspace_bytes) the bf16 kernel uses its faster
+ * fp16-value path.
  *   q, tq        [B, H, Lq,  d]  contiguous, row-major, d fastest
  *   k, v, tk, tv [B, H, Lkv, d]  same
  *   o, to        [B, H, Lq,  d]  float32 (or the input dtype, see attn_jvp_opts.out_dtype)
@@ -30,6 +32,8 @@
  */
 #ifndef ATTN_JVP_H_
 #define ATTN_JVP_H_
+
+#include <stddef.h>
 
 #ifdef __cplusplus
 extern "C" {
@@ -57,17 +61,26 @@ extern "C" {
 /* attn_jvp_opts.flags */
 #define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only: round the weights P~ and H~ = P~ o tS to ONE bf16 term each
                                      (6 matrix products per key tile, as Alg. 2 counts them) instead of the default
-                                     hi + lo bf16 pairs in all three value contractions (9 products).  Faster; the
+                                     hi + lo bf16 pairs in all three value contractions (9 products) or the fp16 value path.  Faster; the
                                      8-bit rounding then shows in the results: max errors up to ~2e-2 of RMS(O) and
                                      a few 1e-2 of RMS(tO) on rows where few keys carry the weight. */
 
+#define ATTN_JVP_FLAG_NO_F16 2    /* MFMA kernel only: do not use the fp16 value path even if a workspace is given */
+
 typedef struct attn_jvp_opts {
-    int   in_dtype;   /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
-    int   out_dtype;  /* ATTN_JVP_OUT_FP32 or ATTN_JVP_OUT_INPUT: dtype of o, to */
-    void* stream;     /* hipStream_t; NULL = the default stream */
-    int   kernel;     /* ATTN_JVP_KERNEL_* */
-    int   flags;      /* bitwise OR of ATTN_JVP_FLAG_*; unknown bits are rejected */
-    int   reserved[3];/* must be zero */
+    int    in_dtype;        /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
+    int    out_dtype;       /* ATTN_JVP_OUT_FP32 or ATTN_JVP_OUT_INPUT: dtype of o, to */
+    void*  stream;          /* hipStream_t; NULL = the default stream */
+    int    kernel;          /* ATTN_JVP_KERNEL_* */
+    int    flags;           /* bitwise OR of ATTN_JVP_FLAG_*; unknown bits are rejected */
+    void*  workspace;       /* optional DEVICE scratch, 256-byte aligned, or NULL.  Contents are overwritten; it
+                               must stay untouched until the call's work on `stream` has finished.  With at least
+                               attn_jvp_workspace_bytes(...) bytes the MFMA kernel runs its fp16 value path: V, tV
+                               are first copied there as per-head power-of-two-scaled fp16, and the weights P~, H~
+                               enter the value contractions as single fp16 terms (6 matrix products per key block,
+                               11-bit weights).  Without it: hi + lo bf16 pairs (9 products, ~16-bit weights). */
+    size_t workspace_bytes; /* size of `workspace` */
+    int    reserved[2];     /* must be zero */
 } attn_jvp_opts;
 
 /*
@@ -85,6 +98,13 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v,
                     void* o, void* to, float* lse,
                     int B, int H, int Lq, int Lkv, int d, float scale,
                     const attn_jvp_opts* opts);
+
+/*
+ * Bytes of scratch the fp16 value path of the MFMA kernel needs for this shape (0 if that path does not exist
+ * for it): 2 fp16 copies of [B,H,Lkv,d] plus 32 bytes of statistics per (batch, head), each part rounded up to
+ * 256 bytes.  Pure host arithmetic.
+ */
+size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 
 /* Static, NUL-terminated description of an error code (never NULL). */
 const char* attn_jvp_strerror(int code);

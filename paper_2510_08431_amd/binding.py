@@ -13,13 +13,15 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libattn_jvp.so")
 
 KERNEL_AUTO, KERNEL_FP32, KERNEL_MFMA = 0, 1, 2
-FLAG_FAST = 1   # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key tile instead of 9)
+FLAG_FAST = 1     # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key block; not tolerance-safe)
+FLAG_NO_F16 = 2   # MFMA kernel: hi + lo bf16 pairs (9 products) even when a workspace is available
 _DTYPE_CODE = {torch.bfloat16: 0, torch.float32: 1}
 
 
 class AttnJvpOpts(ctypes.Structure):
     _fields_ = [("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int), ("stream", ctypes.c_void_p),
-                ("kernel", ctypes.c_int), ("flags", ctypes.c_int), ("reserved", ctypes.c_int * 3)]
+                ("kernel", ctypes.c_int), ("flags", ctypes.c_int), ("workspace", ctypes.c_void_p),
+                ("workspace_bytes", ctypes.c_size_t), ("reserved", ctypes.c_int * 2)]
 
 
 class AttnJvpError(RuntimeError):
@@ -50,6 +52,8 @@ def load_library():
     lib.attn_jvp_strerror.restype = ctypes.c_char_p
     lib.attn_jvp_version.argtypes = []
     lib.attn_jvp_version.restype = ci
+    lib.attn_jvp_workspace_bytes.argtypes = [ci] * 5
+    lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
     _lib = lib
     return lib
 
@@ -60,6 +64,25 @@ def attn_jvp_strerror(code):
 
 def attn_jvp_version():
     return load_library().attn_jvp_version()
+
+
+def attn_jvp_workspace_bytes(B, H, Lq, Lkv, d):
+    return int(load_library().attn_jvp_workspace_bytes(B, H, Lq, Lkv, d))
+
+
+_workspaces = {}
+
+
+def _workspace(device, nbytes):
+    """A per-device scratch tensor from torch's allocator, grown on demand and reused across calls.
+
+    Calls on one device share it: like any torch tensor it is only safe to reuse in stream order, so callers
+    that overlap attention calls on several streams must pass their own `workspace`."""
+    ws = _workspaces.get(device)
+    if ws is None or ws.numel() < nbytes:
+        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _workspaces[device] = ws
+    return ws
 
 
 def _check_inputs(q, k, v, tq, tk, tv):
@@ -82,11 +105,12 @@ def _check_inputs(q, k, v, tq, tk, tv):
 
 
 def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float32, kernel=KERNEL_AUTO, stream=None,
-                    flags=0):
+                    flags=0, workspace="auto"):
     """Enqueue O, tO, lse = attention forward + JVP on the current (or given) stream.
 
     q, tq: [B, H, Lq, d]; k, v, tk, tv: [B, H, Lkv, d]; bf16 or fp32, contiguous, on the GPU.
-    out: optional (o, to, lse) to write into.  Returns (o, to, lse); asynchronous.
+    out: optional (o, to, lse) to write into.  workspace: "auto" (a cached per-device torch buffer), None (no
+    scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  Returns (o, to, lse); asynchronous.
     """
     lib = load_library()
     B, H, Lq, Lkv, d = _check_inputs(q, k, v, tq, tk, tv)
@@ -107,6 +131,12 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     opts.stream = stream.cuda_stream
     opts.kernel = int(kernel)
     opts.flags = int(flags)
+    if isinstance(workspace, str) and workspace == "auto":
+        need = lib.attn_jvp_workspace_bytes(B, H, Lq, Lkv, d) if q.dtype == torch.bfloat16 else 0
+        workspace = _workspace(q.device, need) if need else None
+    if workspace is not None:
+        opts.workspace = workspace.data_ptr()
+        opts.workspace_bytes = workspace.numel() * workspace.element_size()
     with torch.cuda.device(q.device):
         rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
                                  o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale),
@@ -117,5 +147,25 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
 
 
 def attn_jvp_fwd(q, k, v, tq, tk, tv, scale, out=None):
-    """The C entry point `attn_jvp_fwd`: bf16 inputs, fp32 outputs, automatic kernel choice."""
-    return attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=out)
+    """The C entry point `attn_jvp_fwd`: bf16 inputs, fp32 outputs, no workspace, the default stream.
+
+    When torch's current stream is not the default stream the same kernel is enqueued there through
+    `attn_jvp_fwd_ex` instead (no workspace either)."""
+    lib = load_library()
+    B, H, Lq, Lkv, d = _check_inputs(q, k, v, tq, tk, tv)
+    if q.dtype != torch.bfloat16:
+        raise ValueError("attn_jvp_fwd takes bf16 inputs; use attn_jvp_fwd_ex for fp32")
+    if torch.cuda.current_stream(q.device).cuda_stream != 0:
+        return attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=out, workspace=None)
+    if out is None:
+        o = torch.empty(B, H, Lq, d, dtype=torch.float32, device=q.device)
+        to = torch.empty_like(o)
+        lse = torch.empty(B, H, Lq, dtype=torch.float32, device=q.device)
+    else:
+        o, to, lse = out
+    with torch.cuda.device(q.device):
+        rc = lib.attn_jvp_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
+                              o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale))
+    if rc != 0:
+        raise AttnJvpError(rc, attn_jvp_strerror(rc))
+    return o, to, lse

@@ -26,15 +26,17 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     if (elems > 4.0e18L || (long long)B * H > 0x7fffffffLL) return ATTN_JVP_BAD_SHAPE;
     if (opts->in_dtype != ATTN_JVP_BF16 && opts->in_dtype != ATTN_JVP_FP32) return ATTN_JVP_UNSUPPORTED;
     if (opts->out_dtype != ATTN_JVP_OUT_FP32 && opts->out_dtype != ATTN_JVP_OUT_INPUT) return ATTN_JVP_UNSUPPORTED;
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < 2; ++i)
         if (opts->reserved[i] != 0) return ATTN_JVP_UNSUPPORTED;
-    if (opts->flags & ~ATTN_JVP_FLAG_FAST) return ATTN_JVP_UNSUPPORTED;
+    if (opts->flags & ~(ATTN_JVP_FLAG_FAST | ATTN_JVP_FLAG_NO_F16)) return ATTN_JVP_UNSUPPORTED;
+    if (opts->workspace && (reinterpret_cast<uintptr_t>(opts->workspace) & 255u)) return ATTN_JVP_MISALIGNED;
     const void* ptrs[] = {q, k, v, tq, tk, tv, o, to, lse};
     for (const void* p : ptrs)
         if (!aligned16(p)) return ATTN_JVP_MISALIGNED;
 
     Problem p{q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale,
-              opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags};
+              opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags,
+              opts->workspace, opts->workspace ? opts->workspace_bytes : 0};
 
     int kernel = opts->kernel;
     if (kernel == ATTN_JVP_KERNEL_AUTO)
@@ -66,6 +68,11 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v, const void* tq,
                     void* o, void* to, float* lse, int B, int H, int Lq, int Lkv, int d, float scale,
                     const attn_jvp_opts* opts) {
     return run(q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale, opts);
+}
+
+size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
+    if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0 || d != 128) return 0;
+    return attn_jvp::f16_workspace_bytes(B, H, Lkv, d);
 }
 
 const char* attn_jvp_strerror(int code) {

@@ -31,6 +31,7 @@
 // added to a row of tS, and a small |tS - ctr| on the keys that carry the weight keeps the rounding of H~
 // from surviving the B - r O cancellation.
 #include "launchers.h"
+#include "f16_scales.h"
 #include <hip/hip_bf16.h>
 #include <stdint.h>
 #include <type_traits>
@@ -44,10 +45,17 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
 
 constexpr int D = 128, BR = 128, BC = 32, NSTAGE = 4, NTHREADS = 256;
 constexpr int ROW_BYTES = D * 2;
 constexpr int TENSOR_BYTES = BC * ROW_BYTES;            // one tensor's block: 8 KiB
+#ifndef ATTN_JVP_PRESCAN_BLOCKS
+#define ATTN_JVP_PRESCAN_BLOCKS 16
+#endif
+constexpr int PRESCAN_BLOCKS = ATTN_JVP_PRESCAN_BLOCKS;   // key blocks sampled for the fp16 path's exponent reference
 constexpr int KV_STAGE_BYTES = 2 * TENSOR_BYTES;        // K|tK or V|tV
 constexpr int V_RING_BASE = NSTAGE * KV_STAGE_BYTES;    // K ring at [0, 64 KiB), V ring at [64 KiB, 128 KiB)
 constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
@@ -55,6 +63,10 @@ constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
 // nothing may be scheduled across a fence: the instruction order between fences is the issue order
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+// value contractions: bf16 or fp16 operands (the fragments are carried as raw 128-bit registers)
+#define VMFMA(a, b, c)                                                                                          \
+    (F16 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0) \
+         : __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0))
 
 template <int N, typename F, int... I>
 __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
@@ -94,6 +106,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
     v[0] = (__bf16)lo;
     v[1] = (__bf16)hi;
     return __builtin_bit_cast(uint32_t, v);
+}
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
 __device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     u32x4 u = {a, b, c, d};
@@ -166,14 +182,21 @@ __device__ __forceinline__ void issue_pair_full(const char* Xh, const char* tXh,
     }
 }
 
-// SPLIT: the weights P~ and H~ enter all three value contractions as hi + lo bf16 pairs: 9 matrix products per
-// key block instead of Alg. 2's 6, in exchange for ~16-bit instead of 8-bit weights.
-template <bool SPLIT>
+// MODE selects how the weights P~ and H~ enter the three value contractions:
+//   MODE_BF16      one bf16 term each: Alg. 2's 6 matrix products per key block, 8-bit weights;
+//   MODE_BF16_SPLIT hi + lo bf16 pairs: 9 products, ~16-bit weights, no extra memory;
+//   MODE_F16       one fp16 term each against fp16 copies of V, tV (made by the pre-pass, scaled per head by
+//                  powers of two so that nothing over- or underflows): 6 products, 11-bit weights.
+constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2;
+
+template <int MODE>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
-    const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const __hip_bfloat16* __restrict__ V,
-    const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const __hip_bfloat16* __restrict__ tV,
+    const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
+    const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     float* __restrict__ O, float* __restrict__ tO, float* __restrict__ LSE,
-    int Lq, int Lkv, float scale, int q_tiles) {
+    int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats) {
+    constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
+    constexpr bool F16 = MODE == MODE_F16;
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
@@ -187,8 +210,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
     const char* Kh = reinterpret_cast<const char*>(K) + bh * (long)Lkv * ROW_BYTES;
     const char* tKh = reinterpret_cast<const char*>(tK) + bh * (long)Lkv * ROW_BYTES;
-    const char* Vh = reinterpret_cast<const char*>(V) + bh * (long)Lkv * ROW_BYTES;
-    const char* tVh = reinterpret_cast<const char*>(tV) + bh * (long)Lkv * ROW_BYTES;
+    const char* Vh = static_cast<const char*>(V) + bh * (long)Lkv * ROW_BYTES;      // bf16, or the fp16 copies
+    const char* tVh = static_cast<const char*>(tV) + bh * (long)Lkv * ROW_BYTES;
     const int n_blocks = (Lkv + BC - 1) / BC;
 
     // block x: K|tK in K-ring stage x & 3, V|tV in V-ring stage x & 3
@@ -199,8 +222,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         issue_pair_clamped<true>(Vh, tVh, blk * BC, Lkv, lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES,
                                  wave, lane);
     };
-    // start the rings while Q is being fetched (rows past the end are clamped, so all copies are unconditional)
-    copy_k(0); copy_v(0); copy_k(1); copy_v(1); copy_k(2); copy_v(2); copy_k(3);
+    // start the rings while Q is being fetched (rows past the end are clamped, so all copies are unconditional);
+    // the fp16 path first scans a sample of the keys through the K ring (below) and starts the rings after that
+    auto start_rings = [&]() __attribute__((always_inline)) {
+        copy_k(0); copy_v(0); copy_k(1); copy_v(1); copy_k(2); copy_v(2); copy_k(3);
+    };
+    if constexpr (!F16) start_rings();
 
     // Q^T / tQ^T as MFMA B operand: lane (c, g) holds row q0+c, elements 16t + 8g .. +7
     const int qrow = q0 + c;
@@ -237,8 +264,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
 
     const float c2 = scale * 1.4426950408889634f;   // scores -> base-2 exponent
-    float m, ctr;             // per-row exponent reference and tangent-score centre, fixed for the fast sweep
-    float l_part, r_part;     // this lane's share of rowsum(P~) and of rowsum(H~), H~ = P~ o (tS - ctr)
+    float m;                  // per-row exponent reference, fixed for the fast sweep
+    float l_part, r_part;     // this lane's share of rowsum(P~) and of gH * rowsum(H~), H~ = P~ o (tS - ctr)
+    // fp16 path: the O accumulator holds 2^-eV O~, the A+B accumulator 2^-eA (A+B), H~ is formed times gH = 2^(eV-eA)
+    float gO = 1.f, gAB = 1.f, gH = 1.f;
+    if constexpr (F16) {
+        const F16Scales sc = f16_scales(stats + bh * 8, scale);
+        gO = ldexpf(1.f, sc.eV);
+        gAB = ldexpf(1.f, sc.eA);
+        gH = ldexpf(1.f, sc.eV - sc.eA);
+    }
+    const float scale_h = scale * gH;
+    float ctr_h;              // gH * ctr, ctr = per-row centre subtracted from the scaled tangent scores
 
     uint32_t wp[8], wh[8];                              // P~^T, H~^T as packed bf16 pairs, result-register order
     uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT ? 8 : 1];    // their low-order parts
@@ -255,18 +292,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             sp0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
             sp1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
         } else if constexpr (part == 1) {
-            sh0 = sp0 * fmaf(tsv[e], scale, -ctr);
-            sh1 = sp1 * fmaf(tsv[e + 1], scale, -ctr);
+            sh0 = sp0 * fmaf(tsv[e], scale_h, -ctr_h);
+            sh1 = sp1 * fmaf(tsv[e + 1], scale_h, -ctr_h);
         } else if constexpr (part == 2) {
             l_part += sp0 + sp1;
             r_part += sh0 + sh1;
         } else if constexpr (part == 3) {
-            const uint32_t ph = pack_bf16(sp0, sp1);
+            const uint32_t ph = F16 ? pack_f16(sp0, sp1) : pack_bf16(sp0, sp1);
             wp[j] = ph;
             if constexpr (SPLIT)   // lo = x - hi (exact in fp32), rounded to bf16
                 wpl[j] = pack_bf16(sp0 - __uint_as_float(ph << 16), sp1 - __uint_as_float(ph & 0xffff0000u));
         } else if constexpr (part == 4) {
-            const uint32_t hh = pack_bf16(sh0, sh1);
+            const uint32_t hh = F16 ? pack_f16(sh0, sh1) : pack_bf16(sh0, sh1);
             wh[j] = hh;
             if constexpr (SPLIT)
                 whl[j] = pack_bf16(sh0 - __uint_as_float(hh << 16), sh1 - __uint_as_float(hh & 0xffff0000u));
@@ -328,42 +365,84 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 const uint32_t a = vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
                 const bf16x8 vf = join_tr(lds_read_tr_b64(a), lds_read_tr_b64(a + 8 * ROW_BYTES));
                 const bf16x8 tvf = join_tr(lds_read_tr_b64(a + TENSOR_BYTES), lds_read_tr_b64(a + TENSOR_BYTES + 8 * ROW_BYTES));
-                accO[db] = MFMA(vf, pb, accO[db]);
-                accAB[db] = MFMA(tvf, pb, accAB[db]);
-                accAB[db] = MFMA(vf, hb8, accAB[db]);
+                accO[db] = VMFMA(vf, pb, accO[db]);
+                accAB[db] = VMFMA(tvf, pb, accAB[db]);
+                accAB[db] = VMFMA(vf, hb8, accAB[db]);
                 if constexpr (SPLIT) {
                     const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                     const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
-                    accO[db] = MFMA(vf, pl8, accO[db]);
-                    accAB[db] = MFMA(tvf, pl8, accAB[db]);
-                    accAB[db] = MFMA(vf, hl8, accAB[db]);
+                    accO[db] = VMFMA(vf, pl8, accO[db]);
+                    accAB[db] = VMFMA(tvf, pl8, accAB[db]);
+                    accAB[db] = VMFMA(vf, hl8, accAB[db]);
                 }
             }
         }
     };
 
     // ================================ fast sweep ================================
-    // Alg. 2 with the running maximum replaced by a per-row exponent reference fixed after block 0:
-    // m = (block-0 maximum) + REF_HEADROOM.  exp2(S c2 - m) stays representable while later scores exceed
-    // the block-0 maximum by less than ~100 binades, which the sweep verifies at its end (see the check
-    // below); Alg. 2's rescale factors are then all exp(0) = 1 and no accumulator is ever rewritten.
-    // ctr is fixed to block 0's value of rowsum(P o tS).  The loop body is straight-line code.
-    constexpr float REF_HEADROOM = 40.f;   // binades left above the block-0 maximum
+    // Alg. 2 with the running maximum replaced by a per-row exponent reference m fixed before the sweep; Alg. 2's
+    // rescale factors are then all exp(0) = 1 and no accumulator is ever rewritten.  The sweep verifies at its end
+    // that exp2(S c2 - m) stayed representable (see the check below).  ctr is fixed to block 0's value of
+    // rowsum(P o tS).  The loop body is straight-line code.
+    //   bf16 weights: m = block-0 maximum + 40 binades; fine while later scores exceed it by < ~100 binades.
+    //   fp16 weights: P~ must stay below 2^16 and the terms that matter above 2^-14, so m has to be close to the
+    //   true maximum: m = maximum over a sample of ~16 evenly spaced key blocks (first and last included) + 2.
+    constexpr float REF_HEADROOM = F16 ? 2.f : 40.f;
     float headroom = REF_HEADROOM;
+    float m_scan = -INFINITY;
+    if constexpr (F16) {
+        const int step = n_blocks > PRESCAN_BLOCKS ? (n_blocks + PRESCAN_BLOCKS - 1) / PRESCAN_BLOCKS : 1;
+        const int ns = (n_blocks - 1 + step - 1) / step + 1;
+        auto sample_block = [&](int i) -> int { const int x = i * step; return x < n_blocks - 1 ? x : n_blocks - 1; };
+        auto copy_k_only = [&](int i) __attribute__((always_inline)) {   // K rows of sample i into K stage i & 3
+            const int blk = sample_block(i < ns ? i : ns - 1);
+            const uint32_t stage_base = lds0 + (uint32_t)(i & 3) * KV_STAGE_BYTES;
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int rowblk = wave * 2 + r;
+                const int row = rowblk * 4 + (lane >> 4);
+                const int pc = lane & 15;
+                int grow = blk * BC + row;
+                grow = grow < Lkv ? grow : Lkv - 1;
+                ATTN_JVP_LOAD_LDS(Kh + (long)grow * ROW_BYTES + ((pc ^ (row & 15)) << 4), stage_base + rowblk * 1024);
+            }
+        };
+        copy_k_only(0); copy_k_only(1); copy_k_only(2);
+        for (int i = 0; i < ns; ++i) {
+            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // the two newest copies (2 loads each) may be in flight
+            __builtin_amdgcn_s_barrier();
+            copy_k_only(i + 3);
+            const uint32_t off = (uint32_t)(i & 3) * KV_STAGE_BYTES;
+            f32x16 s;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[e] = 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) s = MFMA(lds_read_b128(kaddr0[t] + off), qf[t], s);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { sv[e] = s[e]; tsv[e] = 0.f; }
+            const int blk = sample_block(i);
+            if ((blk + 1) * BC > Lkv) mask_scores(blk);
+            m_scan = fmaxf(m_scan, row_max());
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // everyone is done with the K ring before the real copies start
+        start_rings();
+    }
     {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // K(0..3), V(0..2) and the Q fragments are in
         __syncthreads();
         plain_scores(0);
         if (n_blocks == 1) mask_scores(0);
-        m = row_max() + REF_HEADROOM;
+        m = (F16 ? m_scan : row_max()) + REF_HEADROOM;
         float lb = 0.f, rb = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
             lb += pe;
-            rb = fmaf(pe, tsv[e] * scale, rb);
+            rb = fmaf(pe, tsv[e] * scale_h, rb);
         }
-        ctr = xhalf_sum(rb) / xhalf_sum(lb);
+        const float lb_row = xhalf_sum(lb);
+        ctr_h = lb_row > 0.f ? xhalf_sum(rb) / lb_row : 0.f;
         l_part = 0.f;
         r_part = 0.f;
         static_for<4>([&](auto J) { softmax_pair(J); });   // pairs 0-3 of block 0; pairs 4-7 follow in iteration 0
@@ -496,25 +575,25 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #endif
                 }
             };
-            accO[db] = MFMA(vfr[gi % VRING], pb, accO[db]);
+            accO[db] = VMFMA(vfr[gi % VRING], pb, accO[db]);
             behind(std::integral_constant<int, 0>{});
             FENCE();
-            accAB[db] = MFMA(tvfr[gi % VRING], pb, accAB[db]);
+            accAB[db] = VMFMA(tvfr[gi % VRING], pb, accAB[db]);
             behind(std::integral_constant<int, 1>{});
             FENCE();
-            accAB[db] = MFMA(vfr[gi % VRING], hb8, accAB[db]);
+            accAB[db] = VMFMA(vfr[gi % VRING], hb8, accAB[db]);
             behind(std::integral_constant<int, 2>{});
             if constexpr (SPLIT) {
                 const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                 const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
                 FENCE();
-                accO[db] = MFMA(vfr[gi % VRING], pl8, accO[db]);
+                accO[db] = VMFMA(vfr[gi % VRING], pl8, accO[db]);
                 behind(std::integral_constant<int, 3>{});
                 FENCE();
-                accAB[db] = MFMA(tvfr[gi % VRING], pl8, accAB[db]);
+                accAB[db] = VMFMA(tvfr[gi % VRING], pl8, accAB[db]);
                 behind(std::integral_constant<int, 4>{});
                 FENCE();
-                accAB[db] = MFMA(vfr[gi % VRING], hl8, accAB[db]);
+                accAB[db] = VMFMA(vfr[gi % VRING], hl8, accAB[db]);
             }
             FENCE();
 #ifndef EXP_NO_LOAD
@@ -537,11 +616,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         using U3 = std::integral_constant<int, 3>;
         int b = 0;
         // main loop: every block copied inside it (up to K(b+7)) is a full block
-        for (; b + 8 <= n_full; b += 4) {
-            iteration(U0{}, FY{}, b);
-            iteration(U1{}, FY{}, b + 1);
-            iteration(U2{}, FY{}, b + 2);
-            iteration(U3{}, FY{}, b + 3);
+        if (b + 8 <= n_full) {
+            do {
+                iteration(U0{}, FY{}, b);
+                iteration(U1{}, FY{}, b + 1);
+                iteration(U2{}, FY{}, b + 2);
+                iteration(U3{}, FY{}, b + 3);
+                b += 4;
+            } while (b + 8 <= n_full);
         }
         // tail: clamped copies, and masking of the keys past Lkv in the scores fetched for block b+1
         for (; b < n_blocks; ++b) {
@@ -556,10 +638,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     }
 
     // Did the fixed exponent reference hold?  Row sums beyond 2^60 (or not finite) mean some score exceeded the
-    // block-0 maximum by ~100 binades.  Then the WHOLE workgroup redoes its tile with Alg. 2's running maximum.
+    // reference by ~100 binades.  Then the WHOLE workgroup redoes its tile with Alg. 2's running maximum.
     {
         const float l_chk = xhalf_sum(l_part), r_chk = xhalf_sum(r_part);
-        const bool bad = !(l_chk < 0x1p60f) || !(fabsf(r_chk) < 0x1p100f);
+        bool bad = !(l_chk < 0x1p60f) || !(fabsf(r_chk) < 0x1p100f);
+        if constexpr (F16) {   // an fp16 weight that overflowed (inf) leaves inf or NaN in an accumulator
+            float tot = 0.f;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) tot += fabsf(accO[db][e]) + fabsf(accAB[db][e]);
+            bad = bad || !(tot < 3.0e38f);
+        }
         __syncthreads();                       // everyone is done with the rings
         volatile __attribute__((address_space(3))) int* flag =
             (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds0;
@@ -577,7 +667,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
-            m = -INFINITY; l_part = 0.f; r_part = 0.f; ctr = 0.f; headroom = 0.f;
+            m = -INFINITY; l_part = 0.f; r_part = 0.f; ctr_h = 0.f; headroom = 0.f;
             copy_k(0); copy_v(0);
             for (int b = 0; b < n_blocks; ++b) {
                 const uint32_t off = (uint32_t)(b & 3) * KV_STAGE_BYTES;
@@ -595,14 +685,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 for (int e = 0; e < 16; ++e) {
                     const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
                     lb += pe;
-                    rb = fmaf(pe, fmaf(tsv[e], scale, -ctr), rb);
+                    rb = fmaf(pe, fmaf(tsv[e], scale_h, -ctr_h), rb);
                 }
                 l_part *= alpha;
                 r_part *= alpha;
                 const float l_row = xhalf_sum(l_part + lb);
                 const float r_row = xhalf_sum(r_part + rb);
-                const float delta = r_row / l_row;          // running rowsum(P o tS) minus ctr
-                ctr += delta;
+                const float delta = r_row / l_row;          // gH * (running rowsum(P o tS) minus ctr)
+                ctr_h += delta;
                 r_part = fmaf(-delta, l_part, r_part);
                 const float da = delta * alpha;
 #pragma unroll
@@ -619,11 +709,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         }
     }
 
-    // ---- epilogue: O = O~/l, lse = m + log l, tO = (A + B - (r/l) O~) / l  (r and B both relative to ctr)
+    // ---- epilogue: O = O~/l, lse = m + log l, tO = (A + B - (r/l) O~) / l  (r and B both relative to ctr).
+    // With accO = O~/gO, accAB = (A+B)/gAB and r_part summing gH H~ (gH = gO/gAB) this is gAB (accAB - mu accO) / l.
     const float l_row = xhalf_sum(l_part);
     const float r_row = xhalf_sum(r_part);
     const float inv_l = 1.f / l_row;
     const float mu = r_row * inv_l;
+    const float fo = gO * inv_l, ft = gAB * inv_l;
     if (qrow < Lq) {
         float* Op = O + (bh * Lq + qrow) * D + 4 * g;
         float* tOp = tO + (bh * Lq + qrow) * D + 4 * g;
@@ -633,11 +725,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             for (int v4 = 0; v4 < 4; ++v4) {
                 float4 o4, t4;
                 const float a0 = accO[db][4 * v4], a1 = accO[db][4 * v4 + 1], a2 = accO[db][4 * v4 + 2], a3 = accO[db][4 * v4 + 3];
-                o4.x = a0 * inv_l; o4.y = a1 * inv_l; o4.z = a2 * inv_l; o4.w = a3 * inv_l;
-                t4.x = (accAB[db][4 * v4] - mu * a0) * inv_l;
-                t4.y = (accAB[db][4 * v4 + 1] - mu * a1) * inv_l;
-                t4.z = (accAB[db][4 * v4 + 2] - mu * a2) * inv_l;
-                t4.w = (accAB[db][4 * v4 + 3] - mu * a3) * inv_l;
+                o4.x = a0 * fo; o4.y = a1 * fo; o4.z = a2 * fo; o4.w = a3 * fo;
+                t4.x = (accAB[db][4 * v4] - mu * a0) * ft;
+                t4.y = (accAB[db][4 * v4 + 1] - mu * a1) * ft;
+                t4.z = (accAB[db][4 * v4 + 2] - mu * a2) * ft;
+                t4.w = (accAB[db][4 * v4 + 3] - mu * a3) * ft;
                 *reinterpret_cast<float4*>(Op + 32 * db + 8 * v4) = o4;
                 *reinterpret_cast<float4*>(tOp + 32 * db + 8 * v4) = t4;
             }
@@ -656,18 +748,30 @@ hipError_t launch_mfma_bf16(const Problem& p) {
     const int q_tiles = (p.Lq + BR - 1) / BR;
     const long long blocks = (long long)q_tiles * p.B * p.H;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const void* v = p.v;
+    const void* tv = p.tv;
+    float* stats = nullptr;
     auto launch = [&](auto kern) -> hipError_t {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
-                           (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, (const __hip_bfloat16*)p.v,
-                           (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, (const __hip_bfloat16*)p.tv,
-                           (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles);
+                           (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
+                           (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
+                           (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, (const float*)stats);
         return hipGetLastError();
     };
-    if (p.flags & 1) return launch(attn_jvp_mfma_kernel<false>);
-    return launch(attn_jvp_mfma_kernel<true>);
+    if (p.flags & 1) return launch(attn_jvp_mfma_kernel<MODE_BF16>);
+    // fp16 value path when the caller lent enough scratch (and did not ask for the bf16 pairs)
+    const bool f16 = !(p.flags & 2) && p.workspace != nullptr && (long long)p.B * p.H <= 65535 &&   // pre-pass grid.y
+                     p.workspace_bytes >= f16_workspace_bytes(p.B, p.H, p.Lkv, p.d) &&
+                     (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0;
+    if (f16) {
+        hipError_t e = launch_f16_prepass(p, &stats, &v, &tv);
+        if (e != hipSuccess) return e;
+        return launch(attn_jvp_mfma_kernel<MODE_F16>);
+    }
+    return launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT>);
 }
 
 }  // namespace attn_jvp

@@ -1,0 +1,134 @@
+// Pre-pass of the fp16 value path: per-head statistics, then V, tV -> scaled fp16 copies in the workspace.
+// Both kernels are memory-bound single passes (coalesced 128-bit accesses); together they move
+// 2 (Lq + 3 Lkv) d + 4 Lkv d bytes per head, a few percent of the main kernel's time on long sequences.
+#include "launchers.h"
+#include "f16_scales.h"
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+namespace attn_jvp {
+namespace {
+
+constexpr int D = 128;
+constexpr int ROWS_PER_BLOCK = 256;      // 256 threads: 16 lanes per row, 16 rows per pass
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+__global__ void zero_stats_kernel(float* stats, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) stats[i] = 0.f;
+}
+
+struct StatsArgs {
+    const __hip_bfloat16* x[6];   // V, tV, Q, tQ, K, tK
+    int L[6];
+};
+
+// One launch for all six tensors: blockIdx.z selects the tensor.  Slot 0, 1: abs max of V, tV; slots 2..5: largest
+// squared row norm of Q, tQ, K, tK.
+__global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __restrict__ stats) {
+    const int which = blockIdx.z;
+    const int L = a.L[which];
+    const int row0 = blockIdx.x * ROWS_PER_BLOCK;
+    if (row0 >= L) return;
+    const long bh = blockIdx.y;
+    const __hip_bfloat16* __restrict__ X = a.x[which] + bh * (long)L * D;
+    const int sub = threadIdx.x & 15;            // 16 lanes x 16 B = one 256-byte row
+    const int r_in = threadIdx.x >> 4;
+    float best = 0.f;
+    for (int rr = r_in; rr < ROWS_PER_BLOCK; rr += 64) {
+        uint4 w[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {            // four independent 16-byte loads in flight per lane
+            const int row = row0 + rr + 16 * u;
+            w[u] = row < L ? *reinterpret_cast<const uint4*>(X + (long)row * D + sub * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
+            float v = 0.f;
+            if (which < 2) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v = fmaxf(v, fmaxf(fabsf(bf16_lo(ws[i])), fabsf(bf16_hi(ws[i]))));
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { const float c = bf16_lo(ws[i]), e = bf16_hi(ws[i]); v = fmaf(c, c, fmaf(e, e, v)); }
+                // row norm^2: sum over the 16 lanes of the row
+                v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); v += __shfl_xor(v, 8);
+            }
+            best = fmaxf(best, v);
+        }
+    }
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) best = fmaxf(best, __shfl_xor(best, o));
+    // non-negative floats order like their bit patterns; NaN/inf inputs give a huge pattern and end in the fallback
+    if ((threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<unsigned int*>(stats + bh * 8 + which), __float_as_uint(best));
+}
+
+__global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat16* __restrict__ V,
+                                                             const __hip_bfloat16* __restrict__ tV,
+                                                             const float* __restrict__ stats, __half* __restrict__ V16,
+                                                             __half* __restrict__ tV16, long elems_per_head, float scale) {
+    const long bh = blockIdx.y;
+    const F16Scales sc = f16_scales(stats + bh * 8, scale);
+    const float gV = ldexpf(1.f, -sc.eV), gT = ldexpf(1.f, -sc.eA);
+    const long base = bh * elems_per_head;
+    for (long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < elems_per_head; i += (long)gridDim.x * blockDim.x * 8) {
+        const uint4 a = *reinterpret_cast<const uint4*>(V + base + i);
+        const uint4 b = *reinterpret_cast<const uint4*>(tV + base + i);
+        const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+        __half2 ao[4], bo[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            ao[j] = __floats2half2_rn(bf16_lo(aw[j]) * gV, bf16_hi(aw[j]) * gV);
+            bo[j] = __floats2half2_rn(bf16_lo(bw[j]) * gT, bf16_hi(bw[j]) * gT);
+        }
+        *reinterpret_cast<uint4*>(V16 + base + i) = *reinterpret_cast<const uint4*>(ao);
+        *reinterpret_cast<uint4*>(tV16 + base + i) = *reinterpret_cast<const uint4*>(bo);
+    }
+}
+
+}  // namespace
+
+size_t f16_workspace_bytes(int B, int H, int Lkv, int d) {
+    const size_t heads = (size_t)B * H;
+    const size_t stats = (heads * 8 * sizeof(float) + 255) & ~(size_t)255;
+    const size_t vals = (heads * (size_t)Lkv * d * sizeof(__half) + 255) & ~(size_t)255;
+    return stats + 2 * vals;
+}
+
+hipError_t launch_f16_prepass(const Problem& p, float** stats_out, const void** v16_out, const void** tv16_out) {
+    const size_t heads = (size_t)p.B * p.H;
+    const size_t stats_bytes = (heads * 8 * sizeof(float) + 255) & ~(size_t)255;
+    const size_t vals_bytes = (heads * (size_t)p.Lkv * p.d * sizeof(__half) + 255) & ~(size_t)255;
+    char* ws = static_cast<char*>(p.workspace);
+    float* stats = reinterpret_cast<float*>(ws);
+    __half* V16 = reinterpret_cast<__half*>(ws + stats_bytes);
+    __half* tV16 = reinterpret_cast<__half*>(ws + stats_bytes + vals_bytes);
+    const int n_stats = (int)(heads * 8);
+    hipLaunchKernelGGL(zero_stats_kernel, dim3((n_stats + 255) / 256), dim3(256), 0, p.stream, stats, n_stats);
+    StatsArgs sa;
+    const void* xs[6] = {p.v, p.tv, p.q, p.tq, p.k, p.tk};
+    for (int i = 0; i < 6; ++i) {
+        sa.x[i] = static_cast<const __hip_bfloat16*>(xs[i]);
+        sa.L[i] = (i == 2 || i == 3) ? p.Lq : p.Lkv;
+    }
+    const int Lmax = p.Lq > p.Lkv ? p.Lq : p.Lkv;
+    auto bf = [](const void* x) { return static_cast<const __hip_bfloat16*>(x); };
+    hipLaunchKernelGGL(head_stats_kernel, dim3((Lmax + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, (unsigned)heads, 6), dim3(256), 0,
+                       p.stream, sa, stats);
+    const long eph = (long)p.Lkv * p.d;
+    int cx = (int)((eph / 8 + 255) / 256);
+    if (cx > 512) cx = 512;
+    if (cx < 1) cx = 1;
+    hipLaunchKernelGGL(convert_values_kernel, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), stats,
+                       V16, tV16, eph, p.scale);
+    *stats_out = stats;
+    *v16_out = V16;
+    *tv16_out = tV16;
+    return hipGetLastError();
+}
+
+}  // namespace attn_jvp

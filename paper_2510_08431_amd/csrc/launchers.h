@@ -1,6 +1,7 @@
 // Internal: launcher entry points shared by the C-ABI translation unit and the kernel files.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stddef.h>
 
 namespace attn_jvp {
 
@@ -14,6 +15,8 @@ struct Problem {
     int out_dtype;  // 0 fp32, 1 same as input
     hipStream_t stream;
     int flags;      // ATTN_JVP_FLAG_*
+    void* workspace;        // optional device scratch for the fp16 value path (may be null)
+    size_t workspace_bytes;
 };
 
 // Each returns hipSuccess/hip error of the launch, or hipErrorInvalidValue when the
@@ -22,5 +25,10 @@ hipError_t launch_fp32_vector(const Problem& p);
 hipError_t launch_mfma_bf16(const Problem& p);
 bool mfma_bf16_supports(const Problem& p);
 bool fp32_vector_supports(const Problem& p);
+
+// fp16 value path: bytes of device scratch it needs, and the pre-pass that fills it (per-head statistics at the
+// start of the workspace, then the scaled fp16 copies of V and tV)
+size_t f16_workspace_bytes(int B, int H, int Lkv, int d);
+hipError_t launch_f16_prepass(const Problem& p, float** stats_out, const void** v16_out, const void** tv16_out);
 
 }  // namespace attn_jvp

@@ -82,11 +82,34 @@ def test_fp32_kernel_with_bf16_inputs():
 
 # ------------------------------------------------------------------ bf16 MFMA kernel: shapes and edge cases
 
+# the two tolerance-safe variants of the MFMA kernel: fp16 value path (default when a workspace is available; the
+# binding lends one) and hi + lo bf16 pairs (no workspace)
+VARIANTS = {"f16": 0, "bf16-pairs": binding.FLAG_NO_F16}
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
 @pytest.mark.parametrize("Lq,Lkv", [(1, 1), (32, 64), (128, 64), (128, 65), (200, 333), (129, 127), (31, 1000),
-                                    (517, 4), (384, 640)])
-def test_mfma_kernel_shapes(Lq, Lkv):
+                                    (517, 4), (384, 640), (260, 4100)])
+def test_mfma_kernel_shapes(Lq, Lkv, variant):
     t = random_inputs(300 + Lq + Lkv, 2, 3, Lq, Lkv, 128, torch.bfloat16)
-    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, f"mfma Lq={Lq} Lkv={Lkv}")
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, f"mfma {variant} Lq={Lq} Lkv={Lkv}", flags=VARIANTS[variant])
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("vgain,tgain", [(1e-4, 1e-5), (3e3, 1e4), (1.0, 1e-6), (50.0, 0.0)])
+def test_mfma_value_and_tangent_magnitudes(vgain, tgain, variant):
+    """V and the tangents far from unit scale (the fp16 path rescales per head by powers of two)."""
+    t = random_inputs(77, 1, 2, 200, 700, 128, torch.bfloat16)
+    t["v"] = (t["v"].float() * vgain).to(torch.bfloat16)
+    for n in ("tq", "tk", "tv"):
+        t[n] = (t[n].float() * tgain).to(torch.bfloat16)
+    t["tv"] = (t["tv"].float() * 7.0).to(torch.bfloat16)
+    got = run_gpu(t, 128 ** -0.5, binding.KERNEL_MFMA, VARIANTS[variant])
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], 128 ** -0.5)
+    if tgain == 0.0:
+        assert np.all(got[1] == 0.0)
+        got = (got[0], ref[1], got[2])
+    compare(got, ref, torch.bfloat16, f"magnitudes {variant} v*{vgain} t*{tgain}")
 
 
 # The FAST variant rounds P~ and H~ to single bf16 terms (relative rounding error up to 2^-8 per weight).  Its
@@ -119,7 +142,7 @@ def test_mfma_default_entry_point_and_preallocated_outputs():
     torch.cuda.synchronize()
     out = (torch.full_like(o1, float("nan")), torch.full_like(to1, float("nan")), torch.full_like(lse1, float("nan")))
     binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale, out=out,
-                            kernel=binding.KERNEL_MFMA)
+                            kernel=binding.KERNEL_MFMA, workspace=None)
     torch.cuda.synchronize()
     # same kernel, same inputs: bit-identical (no atomics, fixed summation order)
     assert torch.equal(o1, out[0]) and torch.equal(to1, out[1]) and torch.equal(lse1, out[2])
@@ -142,8 +165,9 @@ def test_mfma_structured_tangents():
     t1 = dict(t0, tv=t["v"])
     o, to, _ = run_gpu(t1, scale, binding.KERNEL_MFMA, binding.FLAG_FAST)
     np.testing.assert_array_equal(to, o)
-    o, to, _ = run_gpu(t1, scale, binding.KERNEL_MFMA)
-    assert rel_err(to, o) <= 1e-4
+    for fl in VARIANTS.values():
+        o, to, _ = run_gpu(t1, scale, binding.KERNEL_MFMA, fl)
+        assert rel_err(to, o) <= 2e-3
     # every key gets the same tangent vector u (tQ = tV = 0): tS is constant along each row, so tO = 0;
     # the kernel reaches it by cancelling B against r*O, which stresses the bf16 rounding of H~
     u = torch.randn(d, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
@@ -215,6 +239,7 @@ def test_mfma_safe_sweep_fallback():
     reference cannot hold, the kernel must notice and redo the tile with the running maximum."""
     t = random_inputs(41, 1, 2, 200, 300, 128, torch.bfloat16)
     t["k"][:, :, 32:] *= 40.0
-    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback")
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, f16")
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, bf16 pairs", flags=binding.FLAG_NO_F16)
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, fast variant", flags=binding.FLAG_FAST,
                tol=FAST_TOL)

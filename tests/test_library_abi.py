@@ -27,9 +27,17 @@ def declared_functions():
 
 def test_header_symbols_exported(lib):
     names = declared_functions()
-    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_strerror", "attn_jvp_version"} <= set(names)
+    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_strerror", "attn_jvp_version", "attn_jvp_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
+
+
+def test_workspace_bytes(lib):
+    lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
+    n = lib.attn_jvp_workspace_bytes(1, 12, 32760, 32760, 128)
+    assert n == 2 * 12 * 32760 * 128 * 2 + 512            # two fp16 copies + 12 x 32 B of statistics (rounded to 256)
+    assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 64) == 0      # no fp16 path for d = 64
+    assert lib.attn_jvp_workspace_bytes(0, 2, 256, 256, 128) == 0
 
 
 def test_version_and_strerror(lib):
@@ -69,8 +77,12 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.kernel = 9
     assert _call(lib, opts=o) == 3
-    o = AttnJvpOpts(); o.reserved[2] = 1
+    o = AttnJvpOpts(); o.reserved[1] = 1
     assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.flags = 8                         # unknown flag bit
+    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.workspace = 0x10010; o.workspace_bytes = 1 << 20   # workspace not 256-byte aligned
+    assert _call(lib, opts=o) == 4
     o = AttnJvpOpts(); o.kernel = 2; o.in_dtype = 1        # MFMA kernel with fp32 inputs
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.kernel = 2                        # MFMA kernel with d = 64
