@@ -80,6 +80,10 @@ typedef struct attn_jvp_opts {
                                enter the value contractions as single fp16 terms (6 matrix products per key block,
                                11-bit weights).  Without it: hi + lo bf16 pairs (9 products, ~16-bit weights). */
     size_t workspace_bytes; /* size of `workspace` */
+    void*  timing_events[2]; /* optional hipEvent_t pair (created by the caller, with timing enabled), or NULL:
+                               [0] is recorded on `stream` immediately before the main attention kernel and [1]
+                               immediately after it, so a profiler can time that kernel apart from the fp16
+                               path's pre-pass kernels, which are enqueued before [0] */
     int    reserved[2];     /* must be zero */
 } attn_jvp_opts;
 

@@ -21,7 +21,8 @@ _DTYPE_CODE = {torch.bfloat16: 0, torch.float32: 1}
 class AttnJvpOpts(ctypes.Structure):
     _fields_ = [("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int), ("stream", ctypes.c_void_p),
                 ("kernel", ctypes.c_int), ("flags", ctypes.c_int), ("workspace", ctypes.c_void_p),
-                ("workspace_bytes", ctypes.c_size_t), ("reserved", ctypes.c_int * 2)]
+                ("workspace_bytes", ctypes.c_size_t), ("timing_events", ctypes.c_void_p * 2),
+                ("reserved", ctypes.c_int * 2)]
 
 
 class AttnJvpError(RuntimeError):
@@ -105,12 +106,14 @@ def _check_inputs(q, k, v, tq, tk, tv):
 
 
 def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float32, kernel=KERNEL_AUTO, stream=None,
-                    flags=0, workspace="auto"):
+                    flags=0, workspace="auto", timing_events=None):
     """Enqueue O, tO, lse = attention forward + JVP on the current (or given) stream.
 
     q, tq: [B, H, Lq, d]; k, v, tk, tv: [B, H, Lkv, d]; bf16 or fp32, contiguous, on the GPU.
     out: optional (o, to, lse) to write into.  workspace: "auto" (a cached per-device torch buffer), None (no
-    scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  Returns (o, to, lse); asynchronous.
+    scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  timing_events: optional pair of
+    torch.cuda.Event(enable_timing=True) that the library records right before and after the main kernel.
+    Returns (o, to, lse); asynchronous.
     """
     lib = load_library()
     B, H, Lq, Lkv, d = _check_inputs(q, k, v, tq, tk, tv)
@@ -137,6 +140,11 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     if workspace is not None:
         opts.workspace = workspace.data_ptr()
         opts.workspace_bytes = workspace.numel() * workspace.element_size()
+    if timing_events is not None:
+        for i, ev in enumerate(timing_events):
+            if not ev.cuda_event:      # torch creates the HIP event lazily, at its first record
+                ev.record(stream)
+            opts.timing_events[i] = ev.cuda_event
     with torch.cuda.device(q.device):
         rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
                                  o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale),

@@ -36,7 +36,8 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
 
     Problem p{q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale,
               opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags,
-              opts->workspace, opts->workspace ? opts->workspace_bytes : 0};
+              opts->workspace, opts->workspace ? opts->workspace_bytes : 0,
+              static_cast<hipEvent_t>(opts->timing_events[0]), static_cast<hipEvent_t>(opts->timing_events[1])};
 
     int kernel = opts->kernel;
     if (kernel == ATTN_JVP_KERNEL_AUTO)

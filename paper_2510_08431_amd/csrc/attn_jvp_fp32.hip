@@ -172,11 +172,12 @@ hipError_t launch_one(const Problem& p) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
+    MainKernelTimer timer(p);
     hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), smem, p.stream,
                        (const TIn*)p.q, (const TIn*)p.k, (const TIn*)p.v,
                        (const TIn*)p.tq, (const TIn*)p.tk, (const TIn*)p.tv,
                        (TOut*)p.o, (TOut*)p.to, p.lse, p.Lq, p.Lkv, p.scale);
-    return hipGetLastError();
+    return timer.finish(hipGetLastError());
 }
 
 template <typename TIn, typename TOut>

@@ -78,18 +78,9 @@ __device__ __forceinline__ void static_for(F&& f) {
 }
 
 __device__ __forceinline__ bf16x8 lds_read_b128(uint32_t addr) {
-#ifdef EXP_NO_LDS
-    u32x4 u = {0x3c003c00u + (addr & 1), 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
-    return __builtin_bit_cast(bf16x8, u);
-#endif
     return *reinterpret_cast<__attribute__((address_space(3))) const bf16x8*>((uintptr_t)addr);
 }
 __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t addr) {
-#ifdef EXP_NO_LDS
-    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_;
-    u32x2_ u = {0x3c003c00u + (addr & 1), 0x3c003c00u};
-    return __builtin_bit_cast(s16x4, u);
-#endif
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
         reinterpret_cast<__attribute__((address_space(3))) s16x4*>((uintptr_t)addr));
 }
@@ -522,31 +513,23 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             using J = std::integral_constant<int, 4 + t / 2>;
             constexpr int s0 = (t % 2) * 3;
             s = MFMA(kfr[t % KRING], qf[t], s);
-#ifndef EXP_NO_SOFTMAX
             softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{});
-#endif
             FENCE();
             ts = MFMA(kfr[t % KRING], tqf[t], ts);
-#ifndef EXP_NO_SOFTMAX
             softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{});
-#endif
             FENCE();
             ts = MFMA(tkfr[t % KRING], qf[t], ts);
-#ifndef EXP_NO_SOFTMAX
             softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{});
-#endif
             FENCE();
             if constexpr (t + KPRE < 8) read_k(std::integral_constant<int, t + KPRE>{}, K1{});
             if constexpr (t >= 8 - VPRE) read_v(std::integral_constant<int, t - (8 - VPRE)>{}, V0{});
             FENCE();
         });
         // ---- middle
-#ifndef EXP_NO_SYNC
         asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // all but the newest copies landed: K(b+2), V(b+1) are in
         // ... and visible to all waves after the barrier; all waves are done with K(b) and V(b-1).  A bare barrier:
         // the LDS reads still in flight (first value fragments of block b) read stages nobody overwrites yet.
         __builtin_amdgcn_s_barrier();
-#endif
         FENCE();
         // ---- phase 2
         static_for<8>([&](auto Gc) {
@@ -570,9 +553,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                         asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]), "+v"(tsv[e0]), "+v"(tsv[e0 + 1]));
                     }
                 } else {
-#ifndef EXP_NO_SOFTMAX
                     softmax_slot(std::integral_constant<int, gi - 4>{}, SLOT, NS_P2{});
-#endif
                 }
             };
             accO[db] = VMFMA(vfr[gi % VRING], pb, accO[db]);
@@ -596,9 +577,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 accAB[db] = VMFMA(vfr[gi % VRING], hl8, accAB[db]);
             }
             FENCE();
-#ifndef EXP_NO_LOAD
             issue_copy_piece(FULLc, Gc, b);
-#endif
             if constexpr (gi + VPRE < 8) read_v(std::integral_constant<int, gi + VPRE>{}, V0{});
             if constexpr (gi >= KFIRST && gi < KFIRST + KPRE) read_k(std::integral_constant<int, gi - KFIRST>{}, K2{});
             FENCE();
@@ -755,11 +734,12 @@ hipError_t launch_mfma_bf16(const Problem& p) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
+        MainKernelTimer timer(p);
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
                            (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, (const float*)stats);
-        return hipGetLastError();
+        return timer.finish(hipGetLastError());
     };
     if (p.flags & 1) return launch(attn_jvp_mfma_kernel<MODE_BF16>);
     // fp16 value path when the caller lent enough scratch (and did not ask for the bf16 pairs)

@@ -17,6 +17,21 @@ struct Problem {
     int flags;      // ATTN_JVP_FLAG_*
     void* workspace;        // optional device scratch for the fp16 value path (may be null)
     size_t workspace_bytes;
+    hipEvent_t ev_start, ev_stop;   // optional: recorded around the main kernel (may be null)
+};
+
+// Records the caller's optional timing events around the main kernel's launch.
+struct MainKernelTimer {
+    const Problem& p;
+    hipError_t err;
+    explicit MainKernelTimer(const Problem& prob) : p(prob), err(hipSuccess) {
+        if (p.ev_start) err = hipEventRecord(p.ev_start, p.stream);
+    }
+    hipError_t finish(hipError_t launch_err) {
+        if (err != hipSuccess) return err;
+        if (launch_err != hipSuccess) return launch_err;
+        return p.ev_stop ? hipEventRecord(p.ev_stop, p.stream) : hipSuccess;
+    }
 };
 
 // Each returns hipSuccess/hip error of the launch, or hipErrorInvalidValue when the

@@ -151,6 +151,23 @@ def test_mfma_default_entry_point_and_preallocated_outputs():
             torch.bfloat16, "default entry point")
 
 
+def test_timing_events_bracket_the_main_kernel():
+    t = random_inputs(12, 1, 2, 1024, 2048, 128, torch.bfloat16)
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    scale = 128 ** -0.5
+    for workspace in ("auto", None):
+        outer = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        inner = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+        outer[0].record()
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                kernel=binding.KERNEL_MFMA, workspace=workspace, timing_events=inner)
+        outer[1].record()
+        torch.cuda.synchronize()
+        ms_inner, ms_outer = inner[0].elapsed_time(inner[1]), outer[0].elapsed_time(outer[1])
+        print(f"[timing events, workspace={workspace}] main kernel {ms_inner:.3f} ms of {ms_outer:.3f} ms", flush=True)
+        assert 0.0 < ms_inner <= ms_outer
+
+
 def test_mfma_structured_tangents():
     B, H, Lq, Lkv, d = 1, 2, 260, 450, 128
     scale = d ** -0.5

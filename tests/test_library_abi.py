@@ -32,6 +32,26 @@ def test_header_symbols_exported(lib):
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
 
+def test_opts_struct_layout_matches_header(tmp_path):
+    """The ctypes mirror of attn_jvp_opts has the size and field offsets a C compiler gives the header's struct."""
+    import subprocess
+    from paper_2510_08431_amd.binding import AttnJvpOpts
+    fields = [n for n, _ in AttnJvpOpts._fields_]
+    src = tmp_path / "layout.c"
+    prints = "\n".join(f'    printf("{n} %zu\\n", offsetof(attn_jvp_opts, {n}));' for n in fields)
+    src.write_text('#include <stdio.h>\n#include <stddef.h>\n#include "attn_jvp.h"\nint main(void) {\n'
+                   '    printf("sizeof %zu\\n", sizeof(attn_jvp_opts));\n' + prints + "\n    return 0;\n}\n")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)],
+                   check=True)
+    got = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True,
+                                                       text=True).stdout.splitlines())
+    assert int(got.pop("sizeof")) == ctypes.sizeof(AttnJvpOpts)
+    assert set(got) == set(fields)
+    for n in fields:
+        assert int(got[n]) == getattr(AttnJvpOpts, n).offset, n
+
+
 def test_workspace_bytes(lib):
     lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
     n = lib.attn_jvp_workspace_bytes(1, 12, 32760, 32760, 128)
