@@ -78,7 +78,10 @@ typedef struct attn_jvp_opts {
                                attn_jvp_workspace_bytes(...) bytes the MFMA kernel runs its fp16 value path: V, tV
                                are first copied there as per-head power-of-two-scaled fp16, and the weights P~, H~
                                enter the value contractions as single fp16 terms (6 matrix products per key block,
-                               11-bit weights).  Without it: hi + lo bf16 pairs (9 products, ~16-bit weights). */
+                               11-bit weights).  Query tiles whose scores are too spread out for fp16 weights
+                               (standard deviation of a row's scaled scores above ~3.3) are done with bf16 pairs
+                               by a second launch.  Without a workspace: hi + lo bf16 pairs everywhere
+                               (9 products, ~16-bit weights). */
     size_t workspace_bytes; /* size of `workspace` */
     void*  timing_events[2]; /* optional hipEvent_t pair (created by the caller, with timing enabled), or NULL:
                                [0] is recorded on `stream` immediately before the main attention kernel and [1]
@@ -105,8 +108,8 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v,
 
 /*
  * Bytes of scratch the fp16 value path of the MFMA kernel needs for this shape (0 if that path does not exist
- * for it): 2 fp16 copies of [B,H,Lkv,d] plus 32 bytes of statistics per (batch, head), each part rounded up to
- * 256 bytes.  Pure host arithmetic.
+ * for it): 2 fp16 copies of [B,H,Lkv,d], 32 bytes of statistics per (batch, head) and 4 bytes per 128-row query
+ * tile, each part rounded up to 256 bytes.  Pure host arithmetic.
  */
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 

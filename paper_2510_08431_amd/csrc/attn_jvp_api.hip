@@ -73,7 +73,7 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v, const void* tq,
 
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
     if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0 || d != 128) return 0;
-    return attn_jvp::f16_workspace_bytes(B, H, Lkv, d);
+    return attn_jvp::f16_workspace_bytes(B, H, Lq, Lkv, d);
 }
 
 const char* attn_jvp_strerror(int code) {

@@ -23,6 +23,11 @@
 // b+1 run over block b's softmax arithmetic, the value MFMAs of block b over the fetch of block b+1's
 // scores from the accumulation registers; LDS fragments are requested several MFMAs ahead of their use.
 //
+// Three instantiations differ in how the weights P~ and H~ enter the three value contractions: single bf16
+// terms (MODE_BF16), hi + lo bf16 pairs (MODE_BF16_SPLIT), or single fp16 terms against power-of-two-scaled fp16
+// copies of V and tV that a pre-pass left in the caller's workspace (MODE_F16).  On the fp16 path the host
+// launches MODE_F16 and then MODE_BF16_SPLIT; per-tile flags in the workspace say which of the two finishes a tile.
+//
 // Numerics: bf16 operands, fp32 accumulation; softmax in base 2 with scale*log2(e) folded into one FMA.
 // The fast sweep fixes the exponent reference m per row after the first block (all of Alg. 2's rescale
 // factors become 1, so the accumulators are only ever written by MFMAs), checks at the end that this was
@@ -185,9 +190,15 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     float* __restrict__ O, float* __restrict__ tO, float* __restrict__ LSE,
-    int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats) {
+    int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16;
+    // Hand-over between the fp16 launch and the bf16-pair launch that follows it on the same stream: the fp16
+    // kernel writes wg_flags[workgroup] = 1 for every tile it declines or abandons (and 0 otherwise) and stores
+    // nothing for those; the pair kernel, given the flags, works on exactly those tiles.
+    if constexpr (!F16) {
+        if (wg_flags != nullptr && wg_flags[blockIdx.x] == 0) return;
+    }
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
@@ -376,12 +387,16 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // that exp2(S c2 - m) stayed representable (see the check below).  ctr is fixed to block 0's value of
     // rowsum(P o tS).  The loop body is straight-line code.
     //   bf16 weights: m = block-0 maximum + 40 binades; fine while later scores exceed it by < ~100 binades.
-    //   fp16 weights: P~ must stay below 2^16 and the terms that matter above 2^-14, so m has to be close to the
-    //   true maximum: m = maximum over a sample of ~16 evenly spaced key blocks (first and last included) + 2.
-    constexpr float REF_HEADROOM = F16 ? 2.f : 40.f;
+    //   fp16 weights: H~ (up to 2^8 P~ after scaling) must stay below 2^16 and the weights that carry the sum
+    //   (some 5 binades below the largest) above 2^-14, so m has to be close to the true maximum:
+    //   m = maximum over a sample of ~16 evenly spaced key blocks (first and last included) + 6 binades.
+    constexpr float REF_HEADROOM = F16 ? 6.f : 40.f;
+    constexpr float F16_MAX_GAP = 13.f;
     float headroom = REF_HEADROOM;
     float m_scan = -INFINITY;
     if constexpr (F16) {
+        float sum1 = 0.f, sum2 = 0.f;   // first and second moment of the sampled raw scores (full blocks only)
+        int n_stat = 0;
         const int step = n_blocks > PRESCAN_BLOCKS ? (n_blocks + PRESCAN_BLOCKS - 1) / PRESCAN_BLOCKS : 1;
         const int ns = (n_blocks - 1 + step - 1) / step + 1;
         auto sample_block = [&](int i) -> int { const int x = i * step; return x < n_blocks - 1 ? x : n_blocks - 1; };
@@ -412,11 +427,45 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sv[e] = s[e]; tsv[e] = 0.f; }
             const int blk = sample_block(i);
-            if ((blk + 1) * BC > Lkv) mask_scores(blk);
+            if ((blk + 1) * BC > Lkv) {
+                mask_scores(blk);
+            } else {
+                float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) { a1 += sv[e]; a2 = fmaf(sv[e], sv[e], a2); }
+                sum1 += a1; sum2 += a2; n_stat += BC;
+            }
             m_scan = fmaxf(m_scan, row_max());
+        }
+        // Is the sampled maximum likely to be close enough to the true one?  fp16 weights tolerate a true maximum
+        // up to ~F16_MAX_GAP binades above the sample's.  For scores with standard deviation sigma the maximum
+        // over all keys exceeds the maximum over a few hundred sampled keys by ~1.2 sigma, rarely by more than
+        // 2.7 sigma; rows with 2.7 sigma above the limit are left to the bf16-pair kernel, which has the exponent
+        // range for them.  The same rule is applied when the sample covers every block and its maximum is exact:
+        // on such peaked rows the 11-bit weights are also the less accurate choice (the rounding of a dominant
+        // key's H~ survives the B - r O cancellation).  A wrong guess costs time only: the end-of-sweep check
+        // catches overflow.
+        bool risky = false;
+        if (n_stat >= BC) {
+            const float inv_n = 1.f / (float)n_stat;
+            const float mean = xhalf_sum(sum1) * inv_n;
+            const float var = fmaxf(xhalf_sum(sum2) * inv_n - mean * mean, 0.f);
+            risky = !(2.7f * __builtin_sqrtf(var) * fabsf(c2) <= F16_MAX_GAP);   // NaN counts as risky
         }
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();   // everyone is done with the K ring before the real copies start
+        volatile __attribute__((address_space(3))) int* flag =
+            (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds0;
+        if (threadIdx.x == 0) *flag = 0;
+        __syncthreads();
+        if (__builtin_amdgcn_ballot_w64(risky) != 0 && lane == 0) *flag = 1;
+        __syncthreads();
+        const bool decline = *flag != 0;
+        __syncthreads();
+        if (decline) {                       // uniform over the workgroup; nothing is in flight
+            if (threadIdx.x == 0) wg_flags[blockIdx.x] = 1;
+            return;
+        }
         start_rings();
     }
     {
@@ -638,7 +687,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         __syncthreads();
         const bool redo = *flag != 0;
         __syncthreads();
-        if (__builtin_expect(redo, 0)) {
+        if constexpr (F16) {
+            // the fp16 kernel does not repair: it hands the tile to the bf16-pair launch that follows
+            if (threadIdx.x == 0) wg_flags[blockIdx.x] = redo ? 1 : 0;
+            if (redo) return;
+        } else if (__builtin_expect(redo, 0)) {
             // ============================ safe sweep (rare) ============================
             // Alg. 2 as printed: per block, running maximum, rescale of every accumulator, no overlap.
             // ctr follows the running value of rowsum(P o tS): B <- B - (ctr_new - ctr_old) O~ keeps it exact.
@@ -727,31 +780,39 @@ hipError_t launch_mfma_bf16(const Problem& p) {
     const int q_tiles = (p.Lq + BR - 1) / BR;
     const long long blocks = (long long)q_tiles * p.B * p.H;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const void* v = p.v;
-    const void* tv = p.tv;
-    float* stats = nullptr;
-    auto launch = [&](auto kern) -> hipError_t {
+    auto launch = [&](auto kern, const void* v, const void* tv, const float* stats, int* wg_flags) -> hipError_t {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
         if (e != hipSuccess) return e;
-        MainKernelTimer timer(p);
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
-                           (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, (const float*)stats);
-        return timer.finish(hipGetLastError());
+                           (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags);
+        return hipGetLastError();
     };
-    if (p.flags & 1) return launch(attn_jvp_mfma_kernel<MODE_BF16>);
-    // fp16 value path when the caller lent enough scratch (and did not ask for the bf16 pairs)
-    const bool f16 = !(p.flags & 2) && p.workspace != nullptr && (long long)p.B * p.H <= 65535 &&   // pre-pass grid.y
-                     p.workspace_bytes >= f16_workspace_bytes(p.B, p.H, p.Lkv, p.d) &&
+    // fp16 value path when the caller lent enough scratch (and did not ask for another variant)
+    const bool f16 = !(p.flags & 3) && p.workspace != nullptr && (long long)p.B * p.H <= 65535 &&   // pre-pass grid.y
+                     p.workspace_bytes >= f16_workspace_bytes(p.B, p.H, p.Lq, p.Lkv, p.d) &&
                      (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0;
+    F16Workspace ws{};
     if (f16) {
-        hipError_t e = launch_f16_prepass(p, &stats, &v, &tv);
+        hipError_t e = launch_f16_prepass(p, &ws);
         if (e != hipSuccess) return e;
-        return launch(attn_jvp_mfma_kernel<MODE_F16>);
     }
-    return launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT>);
+    MainKernelTimer timer(p);
+    hipError_t e;
+    if (p.flags & 1) {
+        e = launch(attn_jvp_mfma_kernel<MODE_BF16>, p.v, p.tv, nullptr, nullptr);
+    } else if (f16) {
+        // every tile is finished by exactly one of the two launches: the fp16 kernel flags the tiles it declines
+        // (scores too spread out for fp16 weights) or abandons (overflow found at the end of its sweep), the
+        // bf16-pair kernel does those and returns at once from the others
+        e = launch(attn_jvp_mfma_kernel<MODE_F16>, ws.v16, ws.tv16, ws.stats, ws.wg_flags);
+        if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT>, p.v, p.tv, nullptr, ws.wg_flags);
+    } else {
+        e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT>, p.v, p.tv, nullptr, nullptr);
+    }
+    return timer.finish(e);
 }
 
 }  // namespace attn_jvp

@@ -92,21 +92,31 @@ __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat1
 
 }  // namespace
 
-size_t f16_workspace_bytes(int B, int H, int Lkv, int d) {
+namespace {
+struct Layout {
+    size_t stats_bytes, flags_bytes, vals_bytes;
+};
+Layout layout(int B, int H, int Lq, int Lkv, int d) {
     const size_t heads = (size_t)B * H;
-    const size_t stats = (heads * 8 * sizeof(float) + 255) & ~(size_t)255;
-    const size_t vals = (heads * (size_t)Lkv * d * sizeof(__half) + 255) & ~(size_t)255;
-    return stats + 2 * vals;
+    const size_t tiles = heads * (size_t)((Lq + MFMA_TILE_ROWS - 1) / MFMA_TILE_ROWS);
+    auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
+    return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)), up(heads * (size_t)Lkv * d * sizeof(__half))};
+}
+}  // namespace
+
+size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
+    const Layout l = layout(B, H, Lq, Lkv, d);
+    return l.stats_bytes + l.flags_bytes + 2 * l.vals_bytes;
 }
 
-hipError_t launch_f16_prepass(const Problem& p, float** stats_out, const void** v16_out, const void** tv16_out) {
+hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out) {
     const size_t heads = (size_t)p.B * p.H;
-    const size_t stats_bytes = (heads * 8 * sizeof(float) + 255) & ~(size_t)255;
-    const size_t vals_bytes = (heads * (size_t)p.Lkv * p.d * sizeof(__half) + 255) & ~(size_t)255;
+    const Layout l = layout(p.B, p.H, p.Lq, p.Lkv, p.d);
     char* ws = static_cast<char*>(p.workspace);
     float* stats = reinterpret_cast<float*>(ws);
-    __half* V16 = reinterpret_cast<__half*>(ws + stats_bytes);
-    __half* tV16 = reinterpret_cast<__half*>(ws + stats_bytes + vals_bytes);
+    int* wg_flags = reinterpret_cast<int*>(ws + l.stats_bytes);
+    __half* V16 = reinterpret_cast<__half*>(ws + l.stats_bytes + l.flags_bytes);
+    __half* tV16 = reinterpret_cast<__half*>(ws + l.stats_bytes + l.flags_bytes + l.vals_bytes);
     const int n_stats = (int)(heads * 8);
     hipLaunchKernelGGL(zero_stats_kernel, dim3((n_stats + 255) / 256), dim3(256), 0, p.stream, stats, n_stats);
     StatsArgs sa;
@@ -125,9 +135,10 @@ hipError_t launch_f16_prepass(const Problem& p, float** stats_out, const void** 
     if (cx < 1) cx = 1;
     hipLaunchKernelGGL(convert_values_kernel, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), stats,
                        V16, tV16, eph, p.scale);
-    *stats_out = stats;
-    *v16_out = V16;
-    *tv16_out = tV16;
+    out->stats = stats;
+    out->wg_flags = wg_flags;
+    out->v16 = V16;
+    out->tv16 = tV16;
     return hipGetLastError();
 }
 

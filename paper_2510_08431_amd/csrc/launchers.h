@@ -41,9 +41,18 @@ hipError_t launch_mfma_bf16(const Problem& p);
 bool mfma_bf16_supports(const Problem& p);
 bool fp32_vector_supports(const Problem& p);
 
-// fp16 value path: bytes of device scratch it needs, and the pre-pass that fills it (per-head statistics at the
-// start of the workspace, then the scaled fp16 copies of V and tV)
-size_t f16_workspace_bytes(int B, int H, int Lkv, int d);
-hipError_t launch_f16_prepass(const Problem& p, float** stats_out, const void** v16_out, const void** tv16_out);
+constexpr int MFMA_TILE_ROWS = 128;   // query rows per workgroup of the MFMA kernel
+
+// fp16 value path: bytes of device scratch it needs, and the pre-pass that fills it.  Workspace layout, each part
+// rounded up to 256 bytes: per-head statistics (8 floats per head) | one int per MFMA workgroup (hand-over flags
+// between the fp16 launch and the bf16-pair launch) | scaled fp16 copy of V | scaled fp16 copy of tV.
+struct F16Workspace {
+    float* stats;
+    int* wg_flags;
+    const void* v16;
+    const void* tv16;
+};
+size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
+hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out);
 
 }  // namespace attn_jvp

@@ -204,6 +204,41 @@ def test_mfma_peaked_softmax_small():
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "peaked softmax L=2048")
 
 
+def f16_tile_flags(B, H, Lq):
+    """Hand-over flags the last fp16-path call left in the binding's cached workspace (one int per 128-row query
+    tile, after the per-head statistics): 1 = tile done by the bf16-pair launch, 0 = done by the fp16 launch."""
+    ws = binding._workspaces[torch.device(DEV)]
+    off = (B * H * 32 + 255) // 256 * 256
+    n = B * H * ((Lq + 127) // 128)
+    return ws[off:off + 4 * n].view(torch.int32).cpu().numpy().reshape(B * H, -1)
+
+
+def test_f16_path_routes_tiles_by_score_spread():
+    """Head 0 has N(0,1) logits (fp16 weights are fine), head 1 logits of std ~8 (sampled maximum unreliable):
+    the fp16 launch must keep the first and hand the second to the bf16-pair launch; both within tolerance."""
+    B, H, Lq, Lkv = 1, 2, 384, 4096
+    t = random_inputs(51, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
+    t["q"][:, 1] *= 8 ** 0.5
+    t["k"][:, 1] *= 8 ** 0.5
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "mixed heads, f16 path")
+    flags = f16_tile_flags(B, H, Lq)
+    print("[tile flags]", flags.tolist(), flush=True)
+    assert (flags[0] == 0).all() and (flags[1] == 1).all()
+
+
+def test_f16_path_abandons_tiles_that_overflow():
+    """One key outside the sampled blocks (key 33; the sample takes every 8th block of 128) scores far above the
+    sampled maximum for about half of the queries: the sample statistics look harmless, the fp16 weights
+    overflow, the end-of-sweep check must notice and the bf16-pair launch must redo those tiles."""
+    B, H, Lq, Lkv = 1, 1, 512, 4096
+    t = random_inputs(52, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
+    t["k"][:, :, 33] *= 24.0
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "outlier key missed by the sample, f16 path")
+    flags = f16_tile_flags(B, H, Lq)
+    print("[tile flags]", flags.tolist(), flush=True)
+    assert (flags == 1).all()
+
+
 # ------------------------------------------------------------------ the five named configurations
 
 def check_config_sampled(cfg, n_random, heads=None):

@@ -55,7 +55,8 @@ def test_opts_struct_layout_matches_header(tmp_path):
 def test_workspace_bytes(lib):
     lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
     n = lib.attn_jvp_workspace_bytes(1, 12, 32760, 32760, 128)
-    assert n == 2 * 12 * 32760 * 128 * 2 + 512            # two fp16 copies + 12 x 32 B of statistics (rounded to 256)
+    # two fp16 copies + 12 x 32 B of statistics (rounded up to 256) + one int per 128-row query tile
+    assert n == 2 * 12 * 32760 * 128 * 2 + 512 + 12 * 256 * 4
     assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 64) == 0      # no fp16 path for d = 64
     assert lib.attn_jvp_workspace_bytes(0, 2, 256, 256, 128) == 0
 
