@@ -54,9 +54,9 @@ extern "C" {
 #define ATTN_JVP_OUT_INPUT 1      /* o, to have the input dtype */
 
 /* attn_jvp_opts.kernel */
-#define ATTN_JVP_KERNEL_AUTO 0    /* bf16 d=128 -> MFMA kernel; everything else -> fp32 vector kernel */
+#define ATTN_JVP_KERNEL_AUTO 0    /* bf16, d=128, scale > 0 -> MFMA kernel; everything else -> fp32 vector kernel */
 #define ATTN_JVP_KERNEL_FP32 1    /* fp32 vector-ALU streaming kernel: any dtype, d in {32, 64, 128, 256}, slow */
-#define ATTN_JVP_KERNEL_MFMA 2    /* bf16 matrix-core kernel: bf16 inputs, d = 128 */
+#define ATTN_JVP_KERNEL_MFMA 2    /* bf16 matrix-core kernel: bf16 inputs, d = 128, scale > 0 */
 
 /* attn_jvp_opts.flags */
 #define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only: round the weights P~ and H~ = P~ o tS to ONE bf16 term each

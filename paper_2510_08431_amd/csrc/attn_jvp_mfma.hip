@@ -64,6 +64,8 @@ constexpr int PRESCAN_BLOCKS = ATTN_JVP_PRESCAN_BLOCKS;   // key blocks sampled 
 constexpr int KV_STAGE_BYTES = 2 * TENSOR_BYTES;        // K|tK or V|tV
 constexpr int V_RING_BASE = NSTAGE * KV_STAGE_BYTES;    // K ring at [0, 64 KiB), V ring at [64 KiB, 128 KiB)
 constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
+static_assert(PRESCAN_BLOCKS >= 2 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES && 2 * PRESCAN_BLOCKS + 16 < 64,
+              "the samples share the ring area, and their loads plus the Q fetch must fit the 6-bit vmcnt counter");
 
 // nothing may be scheduled across a fence: the instruction order between fences is the issue order
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -229,7 +231,30 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     auto start_rings = [&]() __attribute__((always_inline)) {
         copy_k(0); copy_v(0); copy_k(1); copy_v(1); copy_k(2); copy_v(2); copy_k(3);
     };
-    if constexpr (!F16) start_rings();
+    // fp16 path: the K rows of up to PRESCAN_BLOCKS evenly spaced key blocks (first and last included), sample i at
+    // LDS offset i * 8 KiB (the area the rings use later), all requested at once so that one memory latency
+    // covers them and the Q fetch
+    const int ns = n_blocks < PRESCAN_BLOCKS ? n_blocks : PRESCAN_BLOCKS;
+    auto sample_block = [&](int i) -> int {
+        return n_blocks <= PRESCAN_BLOCKS ? i : (int)(((long)i * (n_blocks - 1)) / (PRESCAN_BLOCKS - 1));
+    };
+    if constexpr (F16) {
+        for (int i = 0; i < ns; ++i) {
+            const int blk = sample_block(i);
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                const int rowblk = wave * 2 + r;
+                const int row = rowblk * 4 + (lane >> 4);
+                const int pc = lane & 15;
+                int grow = blk * BC + row;
+                grow = grow < Lkv ? grow : Lkv - 1;
+                ATTN_JVP_LOAD_LDS(Kh + (long)grow * ROW_BYTES + ((pc ^ (row & 15)) << 4),
+                                  lds0 + (uint32_t)i * TENSOR_BYTES + rowblk * 1024);
+            }
+        }
+    } else {
+        start_rings();
+    }
 
     // Q^T / tQ^T as MFMA B operand: lane (c, g) holds row q0+c, elements 16t + 8g .. +7
     const int qrow = q0 + c;
@@ -397,36 +422,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     if constexpr (F16) {
         float sum1 = 0.f, sum2 = 0.f;   // first and second moment of the sampled raw scores (full blocks only)
         int n_stat = 0;
-        const int step = n_blocks > PRESCAN_BLOCKS ? (n_blocks + PRESCAN_BLOCKS - 1) / PRESCAN_BLOCKS : 1;
-        const int ns = (n_blocks - 1 + step - 1) / step + 1;
-        auto sample_block = [&](int i) -> int { const int x = i * step; return x < n_blocks - 1 ? x : n_blocks - 1; };
-        auto copy_k_only = [&](int i) __attribute__((always_inline)) {   // K rows of sample i into K stage i & 3
-            const int blk = sample_block(i < ns ? i : ns - 1);
-            const uint32_t stage_base = lds0 + (uint32_t)(i & 3) * KV_STAGE_BYTES;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                // every wave's share of the samples has landed
+        // Two samples per step, software-pipelined: the sixteen fragment reads of a pair go out together, and the
+        // MFMAs of pair p+1 run while the vector unit works through the statistics of pair p.
+        auto scan_one = [&](const float (&x)[16], int blk) __attribute__((always_inline)) {
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const int rowblk = wave * 2 + r;
-                const int row = rowblk * 4 + (lane >> 4);
-                const int pc = lane & 15;
-                int grow = blk * BC + row;
-                grow = grow < Lkv ? grow : Lkv - 1;
-                ATTN_JVP_LOAD_LDS(Kh + (long)grow * ROW_BYTES + ((pc ^ (row & 15)) << 4), stage_base + rowblk * 1024);
-            }
-        };
-        copy_k_only(0); copy_k_only(1); copy_k_only(2);
-        for (int i = 0; i < ns; ++i) {
-            asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // the two newest copies (2 loads each) may be in flight
-            __builtin_amdgcn_s_barrier();
-            copy_k_only(i + 3);
-            const uint32_t off = (uint32_t)(i & 3) * KV_STAGE_BYTES;
-            f32x16 s;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[e] = 0.f;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) s = MFMA(lds_read_b128(kaddr0[t] + off), qf[t], s);
-#pragma unroll
-            for (int e = 0; e < 16; ++e) { sv[e] = s[e]; tsv[e] = 0.f; }
-            const int blk = sample_block(i);
+            for (int e = 0; e < 16; ++e) { sv[e] = x[e]; tsv[e] = 0.f; }
             if ((blk + 1) * BC > Lkv) {
                 mask_scores(blk);
             } else {
@@ -435,8 +437,38 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 for (int e = 0; e < 16; ++e) { a1 += sv[e]; a2 = fmaf(sv[e], sv[e], a2); }
                 sum1 += a1; sum2 += a2; n_stat += BC;
             }
-            m_scan = fmaxf(m_scan, row_max());
+            float t0 = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
+            float t1 = fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7]));
+            float t2_ = fmaxf(fmaxf(sv[8], sv[9]), fmaxf(sv[10], sv[11]));
+            float t3 = fmaxf(fmaxf(sv[12], sv[13]), fmaxf(sv[14], sv[15]));
+            m_scan = fmaxf(m_scan, fmaxf(fmaxf(t0, t1), fmaxf(t2_, t3)));   // this lane's half of the row, raw
+        };
+        f32x16 s0, s1;
+        auto scores_of_pair = [&](int i) __attribute__((always_inline)) {   // samples i and i+1 (or i twice)
+            const uint32_t off0 = (uint32_t)i * TENSOR_BYTES, off1 = (uint32_t)(i + 1 < ns ? i + 1 : i) * TENSOR_BYTES;
+            bf16x8 ka[8], kb[8];
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { ka[t] = lds_read_b128(kaddr0[t] + off0); kb[t] = lds_read_b128(kaddr0[t] + off1); }
+            FENCE();   // all sixteen reads in flight before the first MFMA waits for one
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { s0[e] = 0.f; s1[e] = 0.f; }
+#pragma unroll
+            for (int t = 0; t < 8; ++t) { s0 = MFMA(ka[t], qf[t], s0); s1 = MFMA(kb[t], qf[t], s1); }
+            FENCE();
+        };
+        scores_of_pair(0);
+        for (int i = 0; i < ns; i += 2) {
+            float x0[16], x1[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { x0[e] = s0[e]; x1[e] = s1[e]; }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) asm volatile("" : "+v"(x0[e]), "+v"(x1[e]));   // copied out before s0, s1 are reused
+            FENCE();
+            if (i + 2 < ns) scores_of_pair(i + 2);
+            scan_one(x0, sample_block(i));
+            if (i + 1 < ns) scan_one(x1, sample_block(i + 1));
         }
+        m_scan = xhalf_max(m_scan) * c2;
         // Is the sampled maximum likely to be close enough to the true one?  fp16 weights tolerate a true maximum
         // up to ~F16_MAX_GAP binades above the sample's.  For scores with standard deviation sigma the maximum
         // over all keys exceeds the maximum over a few hundred sampled keys by ~1.2 sigma, rarely by more than
@@ -452,8 +484,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             const float var = fmaxf(xhalf_sum(sum2) * inv_n - mean * mean, 0.f);
             risky = !(2.7f * __builtin_sqrtf(var) * fabsf(c2) <= F16_MAX_GAP);   // NaN counts as risky
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // everyone is done with the K ring before the real copies start
+        __syncthreads();   // everyone is done with the samples before the ring copies overwrite them
         volatile __attribute__((address_space(3))) int* flag =
             (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds0;
         if (threadIdx.x == 0) *flag = 0;
@@ -653,15 +684,19 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 b += 4;
             } while (b + 8 <= n_full);
         }
-        // tail: clamped copies, and masking of the keys past Lkv in the scores fetched for block b+1
-        for (; b < n_blocks; ++b) {
-            switch (b & 3) {
-                case 0: iteration(U0{}, FN{}, b); break;
-                case 1: iteration(U1{}, FN{}, b); break;
-                case 2: iteration(U2{}, FN{}, b); break;
-                default: iteration(U3{}, FN{}, b); break;
+        // tail (at most 8 blocks, b is a multiple of 4 here): clamped copies, and masking of the keys past Lkv in
+        // the scores fetched for block b+1.  Straight-line nested code, not a loop over a switch: around a loop
+        // the register allocator moved the accumulators at every iteration.
+        auto tail = [&](auto self, auto K, int bb) __attribute__((always_inline)) -> void {
+            constexpr int k = decltype(K)::value;
+            if constexpr (k < 8) {
+                if (bb < n_blocks) {
+                    iteration(std::integral_constant<int, k & 3>{}, FN{}, bb);
+                    self(self, std::integral_constant<int, k + 1>{}, bb + 1);
+                }
             }
-        }
+        };
+        tail(tail, std::integral_constant<int, 0>{}, b);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
 
@@ -773,7 +808,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
 }  // namespace
 
-bool mfma_bf16_supports(const Problem& p) { return p.in_dtype == 0 && p.out_dtype == 0 && p.d == D; }
+// scale > 0: the kernel masks padded keys with a raw score of -inf and takes row maxima before scaling
+bool mfma_bf16_supports(const Problem& p) { return p.in_dtype == 0 && p.out_dtype == 0 && p.d == D && p.scale > 0.f; }
 
 hipError_t launch_mfma_bf16(const Problem& p) {
     if (!mfma_bf16_supports(p)) return hipErrorInvalidValue;

@@ -151,6 +151,18 @@ def test_mfma_default_entry_point_and_preallocated_outputs():
             torch.bfloat16, "default entry point")
 
 
+@pytest.mark.parametrize("scale", [0.0, -0.11])
+def test_non_positive_scale_takes_the_vector_kernel(scale):
+    """The MFMA kernel is written for scale > 0; AUTO must route scale <= 0 (uniform or inverted attention, ragged
+    key tail included) to the fp32 vector kernel, and the result must still match the definition."""
+    t = random_inputs(61, 1, 2, 150, 77, 128, torch.bfloat16)
+    check_full(t, scale, binding.KERNEL_AUTO, f"auto kernel, scale={scale}")
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    with pytest.raises(binding.AttnJvpError):
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                kernel=binding.KERNEL_MFMA)
+
+
 def test_timing_events_bracket_the_main_kernel():
     t = random_inputs(12, 1, 2, 1024, 2048, 128, torch.bfloat16)
     dev = {n: x.to(DEV) for n, x in t.items()}

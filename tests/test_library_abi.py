@@ -108,6 +108,9 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.kernel = 2                        # MFMA kernel with d = 64
     assert _call(lib, dims=(1, 1, 8, 8, 64), opts=o) == 3
+    for bad_scale in (0.0, -0.125):                        # MFMA kernel needs scale > 0 (AUTO then takes the fp32 kernel)
+        o = AttnJvpOpts(); o.kernel = 2
+        assert _call(lib, scale=bad_scale, opts=o) == 3
 
 
 def test_binding_rejects_cpu_tensors_and_bad_shapes():
