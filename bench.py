@@ -25,9 +25,10 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: video-DiT self-attention)")
-    ap.add_argument("--variant", choices=["f16", "bf16-pairs", "fast"], default="f16",
-                    help="MFMA kernel variant: f16 (default: fp16 value path, workspace lent by the binding), "
-                         "bf16-pairs (no workspace), fast (single bf16 weights; outside the tolerance on peaked rows)")
+    ap.add_argument("--variant", choices=["default", "bf16-pairs", "fast"], default="default",
+                    help="MFMA kernel variant: default (workspace lent by the binding: fp16 value path from 2048 keys "
+                         "on, bf16 pairs below), bf16-pairs (no workspace), fast (single bf16 weights; outside the "
+                         "tolerance on peaked rows)")
     ap.add_argument("--fast", action="store_true", help="same as --variant fast")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -67,7 +68,7 @@ def main():
     lse = torch.empty(B, H, Lq, dtype=torch.float32, device=dev)
     if args.fast:
         args.variant = "fast"
-    flags = {"f16": 0, "bf16-pairs": binding.FLAG_NO_F16, "fast": binding.FLAG_FAST}[args.variant]
+    flags = {"default": 0, "bf16-pairs": binding.FLAG_NO_F16, "fast": binding.FLAG_FAST}[args.variant]
 
     def step(events=None):
         binding.attn_jvp_fwd_ex(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], cfg.scale, out=(o, to, lse),

@@ -66,6 +66,9 @@ extern "C" {
                                      a few 1e-2 of RMS(tO) on rows where few keys carry the weight. */
 
 #define ATTN_JVP_FLAG_NO_F16 2    /* MFMA kernel only: do not use the fp16 value path even if a workspace is given */
+#define ATTN_JVP_FLAG_F16_ALWAYS 4 /* MFMA kernel only: use the fp16 value path (given a workspace) for short key
+                                     sequences too; without it Lkv < 2048 takes the bf16 pairs, which are faster
+                                     there (the fp16 path's pre-pass and key sampling do not pay off) */
 
 typedef struct attn_jvp_opts {
     int    in_dtype;        /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
@@ -80,8 +83,8 @@ typedef struct attn_jvp_opts {
                                enter the value contractions as single fp16 terms (6 matrix products per key block,
                                11-bit weights).  Query tiles whose scores are too spread out for fp16 weights
                                (standard deviation of a row's scaled scores above ~3.3) are done with bf16 pairs
-                               by a second launch.  Without a workspace: hi + lo bf16 pairs everywhere
-                               (9 products, ~16-bit weights). */
+                               by a second launch.  Without a workspace, and for Lkv < 2048: hi + lo bf16 pairs
+                               everywhere (9 products, ~16-bit weights). */
     size_t workspace_bytes; /* size of `workspace` */
     void*  timing_events[2]; /* optional hipEvent_t pair (created by the caller, with timing enabled), or NULL:
                                [0] is recorded on `stream` immediately before the main attention kernel and [1]

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libattn_jvp.so")
 
 KERNEL_AUTO, KERNEL_FP32, KERNEL_MFMA = 0, 1, 2
 FLAG_FAST = 1     # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key block; not tolerance-safe)
+FLAG_F16_ALWAYS = 4   # MFMA kernel: fp16 value path also for Lkv < 2048 (given a workspace)
 FLAG_NO_F16 = 2   # MFMA kernel: hi + lo bf16 pairs (9 products) even when a workspace is available
 _DTYPE_CODE = {torch.bfloat16: 0, torch.float32: 1}
 

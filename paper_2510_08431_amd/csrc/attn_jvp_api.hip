@@ -28,7 +28,7 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     if (opts->out_dtype != ATTN_JVP_OUT_FP32 && opts->out_dtype != ATTN_JVP_OUT_INPUT) return ATTN_JVP_UNSUPPORTED;
     for (int i = 0; i < 2; ++i)
         if (opts->reserved[i] != 0) return ATTN_JVP_UNSUPPORTED;
-    if (opts->flags & ~(ATTN_JVP_FLAG_FAST | ATTN_JVP_FLAG_NO_F16)) return ATTN_JVP_UNSUPPORTED;
+    if (opts->flags & ~(ATTN_JVP_FLAG_FAST | ATTN_JVP_FLAG_NO_F16 | ATTN_JVP_FLAG_F16_ALWAYS)) return ATTN_JVP_UNSUPPORTED;
     if (opts->workspace && (reinterpret_cast<uintptr_t>(opts->workspace) & 255u)) return ATTN_JVP_MISALIGNED;
     const void* ptrs[] = {q, k, v, tq, tk, tv, o, to, lse};
     for (const void* p : ptrs)

@@ -186,6 +186,7 @@ __device__ __forceinline__ void issue_pair_full(const char* Xh, const char* tXh,
 //   MODE_F16       one fp16 term each against fp16 copies of V, tV (made by the pre-pass, scaled per head by
 //                  powers of two so that nothing over- or underflows): 6 products, 11-bit weights.
 constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2;
+constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
 template <int MODE>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
@@ -826,8 +827,10 @@ hipError_t launch_mfma_bf16(const Problem& p) {
                            (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags);
         return hipGetLastError();
     };
-    // fp16 value path when the caller lent enough scratch (and did not ask for another variant)
+    // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence
+    // is long enough to amortise its per-call pre-pass and per-tile key sampling (measured break-even ~1500 keys)
     const bool f16 = !(p.flags & 3) && p.workspace != nullptr && (long long)p.B * p.H <= 65535 &&   // pre-pass grid.y
+                     (p.Lkv >= F16_MIN_KEYS || (p.flags & 4)) &&
                      p.workspace_bytes >= f16_workspace_bytes(p.B, p.H, p.Lq, p.Lkv, p.d) &&
                      (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0;
     F16Workspace ws{};

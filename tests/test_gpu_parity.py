@@ -84,7 +84,10 @@ def test_fp32_kernel_with_bf16_inputs():
 
 # the two tolerance-safe variants of the MFMA kernel: fp16 value path (default when a workspace is available; the
 # binding lends one) and hi + lo bf16 pairs (no workspace)
-VARIANTS = {"f16": 0, "bf16-pairs": binding.FLAG_NO_F16}
+VARIANTS = {"f16": binding.FLAG_F16_ALWAYS, "bf16-pairs": binding.FLAG_NO_F16}
+# on the named configurations: the launch configuration bench.py times (default flags: fp16 path from 2048 keys on,
+# pairs below) and the pairs everywhere
+CONFIG_VARIANTS = {"default": 0, "bf16-pairs": binding.FLAG_NO_F16}
 
 
 @pytest.mark.parametrize("variant", list(VARIANTS))
@@ -187,7 +190,7 @@ def test_mfma_structured_tangents():
     z = lambda x: torch.zeros_like(x)
     # zero tangents: tO is exactly zero
     t0 = dict(t, tq=z(t["tq"]), tk=z(t["tk"]), tv=z(t["tv"]))
-    o, to, _ = run_gpu(t0, scale, binding.KERNEL_MFMA)
+    o, to, _ = run_gpu(t0, scale, binding.KERNEL_MFMA, binding.FLAG_F16_ALWAYS)
     assert np.all(to == 0.0)
     # tV = V, tQ = tK = 0: tO = O.  In the FAST variant both come from the same products in the same order
     # (bit-identical); the default variant gives O the extra low-order term of P~, so they agree to rounding.
@@ -201,7 +204,7 @@ def test_mfma_structured_tangents():
     # the kernel reaches it by cancelling B against r*O, which stresses the bf16 rounding of H~
     u = torch.randn(d, generator=torch.Generator().manual_seed(5)).to(torch.bfloat16)
     t2 = dict(t0, tk=u.expand(B, H, Lkv, d).contiguous())
-    got = run_gpu(t2, scale, binding.KERNEL_MFMA)
+    got = run_gpu(t2, scale, binding.KERNEL_MFMA, binding.FLAG_F16_ALWAYS)
     ref = attn_jvp_ref(t2["q"], t2["k"], t2["v"], t2["tq"], t2["tk"], t2["tv"], scale)
     o_rms = np.sqrt((ref[0] ** 2).mean())
     ts_rms = float((t["q"].double() @ u.double()).pow(2).mean().sqrt()) * scale
@@ -257,7 +260,7 @@ def check_config_sampled(cfg, n_random, heads=None):
     """Full-size launches (every tolerance-safe variant of the kernel the configuration runs on); oracle on a
     seeded sample of query rows of every (or the given) head, computed once and compared with each variant."""
     t = make_inputs(cfg)
-    variants = VARIANTS if cfg.dtype == "bf16" and cfg.d == 128 else {"auto": 0}
+    variants = CONFIG_VARIANTS if cfg.dtype == "bf16" and cfg.d == 128 else {"auto": 0}
     got = {name: run_gpu(t, cfg.scale, flags=fl) for name, fl in variants.items()}
     rows = sample_rows(cfg, n_random)
     worst = {name: [0.0, 0.0] for name in variants}
@@ -291,11 +294,11 @@ def test_config3_video_self():
 def test_config4_video_cross_all_rows():
     cfg = CONFIGS[4]
     t = make_inputs(cfg)
-    got = {name: run_gpu(t, cfg.scale, flags=fl) for name, fl in VARIANTS.items()}
+    got = {name: run_gpu(t, cfg.scale, flags=fl) for name, fl in CONFIG_VARIANTS.items()}
     for h in range(cfg.H):
         sl = lambda x: x[:, h:h + 1]
         ref = attn_jvp_ref(sl(t["q"]), sl(t["k"]), sl(t["v"]), sl(t["tq"]), sl(t["tk"]), sl(t["tv"]), cfg.scale)
-        for name in VARIANTS:
+        for name in CONFIG_VARIANTS:
             compare(tuple(x[:, h:h + 1] for x in got[name]), ref, cfg.torch_dtype, f"cfg4 {name} h{h}")
 
 
@@ -308,7 +311,8 @@ def test_mfma_safe_sweep_fallback():
     reference cannot hold, the kernel must notice and redo the tile with the running maximum."""
     t = random_inputs(41, 1, 2, 200, 300, 128, torch.bfloat16)
     t["k"][:, :, 32:] *= 40.0
-    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, f16")
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, f16 path (declined, then pairs)",
+               flags=binding.FLAG_F16_ALWAYS)
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, bf16 pairs", flags=binding.FLAG_NO_F16)
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, fast variant", flags=binding.FLAG_FAST,
                tol=FAST_TOL)
