@@ -30,6 +30,9 @@ def main():
                          "on, bf16 pairs below), bf16-pairs (no workspace), fast (single bf16 weights; outside the "
                          "tolerance on peaked rows)")
     ap.add_argument("--fast", action="store_true", help="same as --variant fast")
+    ap.add_argument("--null-kv-tangents", action="store_true",
+                    help="pass tk = tv = NULL instead of the tensors (only meaningful where they are zero: config 4); "
+                         "the kernel then executes 8*Lq*Lkv*d flop per head, the metric still counts 12")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (known traffic) for scaling HBM counters")
@@ -70,8 +73,13 @@ def main():
         args.variant = "fast"
     flags = {"default": 0, "bf16-pairs": binding.FLAG_NO_F16, "fast": binding.FLAG_FAST}[args.variant]
 
+    if args.null_kv_tangents and (t["tk"].any() or t["tv"].any()):
+        print("bench.py: --null-kv-tangents needs a workload whose tk and tv are zero (config 4)", file=sys.stderr)
+        sys.exit(2)
+    tk, tv = (None, None) if args.null_kv_tangents else (t["tk"], t["tv"])
+
     def step(events=None):
-        binding.attn_jvp_fwd_ex(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], cfg.scale, out=(o, to, lse),
+        binding.attn_jvp_fwd_ex(t["q"], t["k"], t["v"], t["tq"], tk, tv, cfg.scale, out=(o, to, lse),
                                 flags=flags, timing_events=events)
 
     for _ in range(args.warmup):
@@ -108,7 +116,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
-                   "variant": args.variant},
+                   "variant": args.variant, "kv_tangents": "null" if args.null_kv_tangents else "tensors"},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,

@@ -87,12 +87,20 @@ def _workspace(device, nbytes):
     return ws
 
 
+def _ptr(t):
+    return t.data_ptr() if t is not None else None
+
+
 def _check_inputs(q, k, v, tq, tk, tv):
     if q.dim() != 4:
         raise ValueError("q must be [B, H, Lq, d]")
     B, H, Lq, d = q.shape
     Lkv = k.shape[2]
+    if (tk is None) != (tv is None):
+        raise ValueError("tk and tv must both be given or both be None (zero key/value tangents)")
     for name, t, L in (("q", q, Lq), ("tq", tq, Lq), ("k", k, Lkv), ("v", v, Lkv), ("tk", tk, Lkv), ("tv", tv, Lkv)):
+        if t is None:
+            continue
         if tuple(t.shape) != (B, H, L, d):
             raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {(B, H, L, d)}")
         if t.dtype != q.dtype or t.device != q.device:
@@ -110,7 +118,8 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
                     flags=0, workspace="auto", timing_events=None):
     """Enqueue O, tO, lse = attention forward + JVP on the current (or given) stream.
 
-    q, tq: [B, H, Lq, d]; k, v, tk, tv: [B, H, Lkv, d]; bf16 or fp32, contiguous, on the GPU.
+    q, tq: [B, H, Lq, d]; k, v, tk, tv: [B, H, Lkv, d]; bf16 or fp32, contiguous, on the GPU.  tk and tv may both be
+    None: zero key/value tangents (cross-attention onto a context without tangent).
     out: optional (o, to, lse) to write into.  workspace: "auto" (a cached per-device torch buffer), None (no
     scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  timing_events: optional pair of
     torch.cuda.Event(enable_timing=True) that the library records right before and after the main kernel.
@@ -147,7 +156,7 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
                 ev.record(stream)
             opts.timing_events[i] = ev.cuda_event
     with torch.cuda.device(q.device):
-        rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
+        rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), _ptr(tk), _ptr(tv),
                                  o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale),
                                  ctypes.byref(opts))
     if rc != 0:
@@ -173,7 +182,7 @@ def attn_jvp_fwd(q, k, v, tq, tk, tv, scale, out=None):
     else:
         o, to, lse = out
     with torch.cuda.device(q.device):
-        rc = lib.attn_jvp_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), tk.data_ptr(), tv.data_ptr(),
+        rc = lib.attn_jvp_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), _ptr(tk), _ptr(tv),
                               o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale))
     if rc != 0:
         raise AttnJvpError(rc, attn_jvp_strerror(rc))

@@ -18,7 +18,8 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     def.out_dtype = ATTN_JVP_OUT_FP32;
     if (!opts) opts = &def;
 
-    if (!q || !k || !v || !tq || !tk || !tv || !o || !to || !lse) return ATTN_JVP_NULL_PTR;
+    if (!q || !k || !v || !tq || !o || !to || !lse) return ATTN_JVP_NULL_PTR;
+    if ((tk == nullptr) != (tv == nullptr)) return ATTN_JVP_NULL_PTR;   // zero key/value tangents come as a pair
     if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0 || d <= 0) return ATTN_JVP_BAD_SHAPE;
     if (!std::isfinite(scale)) return ATTN_JVP_BAD_SHAPE;
     // element counts must stay far below 2^62 so that byte offsets fit in 64 bits; B*H must fit a grid dimension

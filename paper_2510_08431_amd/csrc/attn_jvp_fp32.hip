@@ -89,9 +89,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
             krow = krow < Lkv ? krow : Lkv - 1;  // pad rows duplicate the last key; masked below
             long off = (long)krow * D + 4 * cc;
             sK[idx] = Ld<TIn>::load4(Kb + off);
-            stK[idx] = Ld<TIn>::load4(tKb + off);
+            stK[idx] = tK ? Ld<TIn>::load4(tKb + off) : make_float4(0.f, 0.f, 0.f, 0.f);   // absent tangents are zero
             sV[idx] = Ld<TIn>::load4(Vb + off);
-            stV[idx] = Ld<TIn>::load4(tVb + off);
+            stV[idx] = tV ? Ld<TIn>::load4(tVb + off) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         __syncthreads();
 

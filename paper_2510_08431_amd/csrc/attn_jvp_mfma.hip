@@ -139,7 +139,7 @@ __device__ __forceinline__ void load_lds_b128(const void* uniform_base, uint32_t
 // applied by choosing which 16-byte chunk of the row each lane fetches: K, tK: chunk ^= row & 15 (row-wise b128
 // reads); V, tV (VSWZ): chunk ^= (row & 3) << 2 (transposing b64 reads).  Rows past Lkv re-read the last valid
 // row (finite values; their scores are masked to -inf).
-template <bool VSWZ>
+template <bool VSWZ, bool WITH_TANGENT>
 __device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* tXh, int j0, int Lkv,
                                                    uint32_t stage_base, int wave, int lane) {
 #pragma unroll
@@ -152,7 +152,7 @@ __device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* t
         const long goff = (long)grow * ROW_BYTES + ((VSWZ ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15))) << 4);
         const uint32_t dst = stage_base + rowblk * 1024;
         ATTN_JVP_LOAD_LDS(Xh + goff, dst);
-        ATTN_JVP_LOAD_LDS(tXh + goff, dst + TENSOR_BYTES);
+        if constexpr (WITH_TANGENT) ATTN_JVP_LOAD_LDS(tXh + goff, dst + TENSOR_BYTES);
     }
 }
 // Same copy for a block known to lie entirely inside the sequence: the per-lane byte offsets (row and swizzled
@@ -169,26 +169,20 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane) {
     }
     return o;
 }
-__device__ __forceinline__ void issue_pair_full(const char* Xh, const char* tXh, int blk, const uint32_t (&lo)[2],
-                                                uint32_t stage_base, int wave) {
-    const long boff = (long)blk * (BC * ROW_BYTES);
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const uint32_t dst = stage_base + (wave * 2 + i) * 1024;
-        ATTN_JVP_LOAD_LDS(Xh + boff + lo[i], dst);
-        ATTN_JVP_LOAD_LDS(tXh + boff + lo[i], dst + TENSOR_BYTES);
-    }
-}
 
 // MODE selects how the weights P~ and H~ enter the three value contractions:
 //   MODE_BF16      one bf16 term each: Alg. 2's 6 matrix products per key block, 8-bit weights;
 //   MODE_BF16_SPLIT hi + lo bf16 pairs: 9 products, ~16-bit weights, no extra memory;
 //   MODE_F16       one fp16 term each against fp16 copies of V, tV (made by the pre-pass, scaled per head by
 //                  powers of two so that nothing over- or underflows): 6 products, 11-bit weights.
+//
+// ZT ("zero key/value tangents", cross-attention onto a context that does not depend on the differentiated
+// variable): tK = tV = 0 are not passed at all.  tS = scale tQ K^T and tO = tP V then need 4 of the 6 products, and
+// only K and V are streamed; the stage layout stays the same, the tangent halves are simply never written or read.
 constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2;
 constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
-template <int MODE>
+template <int MODE, bool ZT>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
@@ -221,11 +215,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
     // block x: K|tK in K-ring stage x & 3, V|tV in V-ring stage x & 3
     auto copy_k = [&](int blk) __attribute__((always_inline)) {
-        issue_pair_clamped<false>(Kh, tKh, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
+        issue_pair_clamped<false, !ZT>(Kh, tKh, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
     auto copy_v = [&](int blk) __attribute__((always_inline)) {
-        issue_pair_clamped<true>(Vh, tVh, blk * BC, Lkv, lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES,
-                                 wave, lane);
+        issue_pair_clamped<true, !ZT>(Vh, tVh, blk * BC, Lkv,
+                                      lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
     // start the rings while Q is being fetched (rows past the end are clamped, so all copies are unconditional);
     // the fp16 path first scans a sample of the keys through the K ring (below) and starts the rings after that
@@ -340,16 +334,27 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     auto softmax_pair = [&](auto J) __attribute__((always_inline)) {
         static_for<5>([&](auto PART) { softmax_part(J, PART); });
     };
-    // the part that goes behind MFMA number `slot` of the `n_slots` (3 or 6) a pair has to itself
+    // the part(s) that go behind MFMA number `slot` of the `n_slots` a pair has to itself
     auto softmax_slot = [&](auto J, auto SLOT, auto NSLOTS) __attribute__((always_inline)) {
         constexpr int slot = decltype(SLOT)::value, n_slots = decltype(NSLOTS)::value;
         if constexpr (n_slots >= 5) {
             if constexpr (slot < 5) softmax_part(J, SLOT);
-        } else {
-            static_assert(n_slots == 3, "a pair gets 3 or at least 5 MFMA slots");
+        } else if constexpr (n_slots == 4) {
+            if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{});
+            if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}); softmax_part(J, std::integral_constant<int, 2>{}); }
+            if constexpr (slot == 2) softmax_part(J, std::integral_constant<int, 3>{});
+            if constexpr (slot == 3) softmax_part(J, std::integral_constant<int, 4>{});
+        } else if constexpr (n_slots == 3) {
             if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{});
             if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}); softmax_part(J, std::integral_constant<int, 3>{}); }
             if constexpr (slot == 2) { softmax_part(J, std::integral_constant<int, 2>{}); softmax_part(J, std::integral_constant<int, 4>{}); }
+        } else {
+            static_assert(n_slots == 2, "a pair gets 2, 3, 4 or at least 5 MFMA slots");
+            if constexpr (slot == 0) { softmax_part(J, std::integral_constant<int, 0>{}); softmax_part(J, std::integral_constant<int, 1>{}); }
+            if constexpr (slot == 1) {
+                softmax_part(J, std::integral_constant<int, 2>{}); softmax_part(J, std::integral_constant<int, 3>{});
+                softmax_part(J, std::integral_constant<int, 4>{});
+            }
         }
     };
 
@@ -368,10 +373,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #pragma unroll
         for (int t = 0; t < 8; ++t) {
             const bf16x8 kf = lds_read_b128(kaddr0[t] + stage_off);
-            const bf16x8 tkf = lds_read_b128(kaddr0[t] + stage_off + TENSOR_BYTES);
             s = MFMA(kf, qf[t], s);
             ts = MFMA(kf, tqf[t], ts);
-            ts = MFMA(tkf, qf[t], ts);
+            if constexpr (!ZT) ts = MFMA(lds_read_b128(kaddr0[t] + stage_off + TENSOR_BYTES), qf[t], ts);
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) { sv[e] = s[e]; tsv[e] = ts[e]; }
@@ -392,15 +396,17 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             for (int db = 0; db < 4; ++db) {
                 const uint32_t a = vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
                 const bf16x8 vf = join_tr(lds_read_tr_b64(a), lds_read_tr_b64(a + 8 * ROW_BYTES));
-                const bf16x8 tvf = join_tr(lds_read_tr_b64(a + TENSOR_BYTES), lds_read_tr_b64(a + TENSOR_BYTES + 8 * ROW_BYTES));
+                bf16x8 tvf = vf;   // placeholder when there is no tV
+                if constexpr (!ZT)
+                    tvf = join_tr(lds_read_tr_b64(a + TENSOR_BYTES), lds_read_tr_b64(a + TENSOR_BYTES + 8 * ROW_BYTES));
                 accO[db] = VMFMA(vf, pb, accO[db]);
-                accAB[db] = VMFMA(tvf, pb, accAB[db]);
+                if constexpr (!ZT) accAB[db] = VMFMA(tvf, pb, accAB[db]);
                 accAB[db] = VMFMA(vf, hb8, accAB[db]);
                 if constexpr (SPLIT) {
                     const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                     const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
                     accO[db] = VMFMA(vf, pl8, accO[db]);
-                    accAB[db] = VMFMA(tvf, pl8, accAB[db]);
+                    if constexpr (!ZT) accAB[db] = VMFMA(tvf, pl8, accAB[db]);
                     accAB[db] = VMFMA(vf, hl8, accAB[db]);
                 }
             }
@@ -536,15 +542,16 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         constexpr int t = decltype(T)::value;
         constexpr int off = decltype(ST)::value * KV_STAGE_BYTES;
         kfr[t % KRING] = lds_read_b128(kaddr0[t] + off);
-        tkfr[t % KRING] = lds_read_b128(kaddr0[t] + off + TENSOR_BYTES);
+        if constexpr (!ZT) tkfr[t % KRING] = lds_read_b128(kaddr0[t] + off + TENSOR_BYTES);
     };
     auto read_v = [&](auto G, auto ST) __attribute__((always_inline)) {     // value group G of the block in V stage ST
         constexpr int gi = decltype(G)::value;
         constexpr int t2 = gi >> 2, db = gi & 3;
         constexpr int off = decltype(ST)::value * KV_STAGE_BYTES + t2 * 16 * ROW_BYTES;
         vfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off), lds_read_tr_b64(vaddr0[db] + off + 8 * ROW_BYTES));
-        tvfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES),
-                                   lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES + 8 * ROW_BYTES));
+        if constexpr (!ZT)
+            tvfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES),
+                                       lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES + 8 * ROW_BYTES));
     };
 
     // The copies of iteration b: K(b+4) into K stage b & 3, V(b+3) into V stage (b+3) & 3, as 8 direct-to-LDS
@@ -554,6 +561,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     auto issue_copy_piece = [&](auto FULLc, auto IDX, int b) __attribute__((always_inline)) {
         constexpr int idx = decltype(IDX)::value;
         constexpr int i = idx >> 2, which = idx & 3;      // row group of this wave; 0 K, 1 tK, 2 V, 3 tV
+        if constexpr (ZT && (which & 1)) return;          // no tangent tensors to copy
         const int blk = which < 2 ? b + 4 : b + 3;
         const char* base = which == 0 ? Kh : which == 1 ? tKh : which == 2 ? Vh : tVh;
         const uint32_t dst = lds0 + (which < 2 ? 0 : V_RING_BASE) + (uint32_t)(blk & 3) * KV_STAGE_BYTES +
@@ -579,8 +587,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     auto iteration = [&](auto Uc, auto FULLc, int b) __attribute__((always_inline)) {
         constexpr int U = decltype(Uc)::value;
         constexpr bool FULL = decltype(FULLc)::value;
-        constexpr int GROUP_MFMAS = SPLIT ? 6 : 3;
-        using NS_P1 = std::integral_constant<int, 6>;             // phase 1: two score steps (6 MFMAs) per pair
+        constexpr int PRODUCTS = ZT ? 2 : 3;                      // matrix products per score step / per weight term
+        constexpr int GROUP_MFMAS = SPLIT ? 2 * PRODUCTS : PRODUCTS;
+        using NS_P1 = std::integral_constant<int, 2 * PRODUCTS>;  // phase 1: two score steps per pair
         using NS_P2 = std::integral_constant<int, GROUP_MFMAS>;   // phase 2: one value group per pair
         using K1 = std::integral_constant<int, (U + 1) & 3>;    // K stage of block b+1
         using K2 = std::integral_constant<int, (U + 2) & 3>;    // K stage of block b+2
@@ -592,22 +601,26 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         static_for<8>([&](auto T) {
             constexpr int t = decltype(T)::value;
             using J = std::integral_constant<int, 4 + t / 2>;
-            constexpr int s0 = (t % 2) * 3;
+            constexpr int s0 = (t % 2) * PRODUCTS;
             s = MFMA(kfr[t % KRING], qf[t], s);
             softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{});
             FENCE();
             ts = MFMA(kfr[t % KRING], tqf[t], ts);
             softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{});
             FENCE();
-            ts = MFMA(tkfr[t % KRING], qf[t], ts);
-            softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{});
-            FENCE();
+            if constexpr (!ZT) {
+                ts = MFMA(tkfr[t % KRING], qf[t], ts);
+                softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{});
+                FENCE();
+            }
             if constexpr (t + KPRE < 8) read_k(std::integral_constant<int, t + KPRE>{}, K1{});
             if constexpr (t >= 8 - VPRE) read_v(std::integral_constant<int, t - (8 - VPRE)>{}, V0{});
             FENCE();
         });
         // ---- middle
-        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // all but the newest copies landed: K(b+2), V(b+1) are in
+        // all but the newest copies (8 instructions per wave and iteration, 4 without tangents) landed: K(b+2), V(b+1) are in
+        if constexpr (ZT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
         // ... and visible to all waves after the barrier; all waves are done with K(b) and V(b-1).  A bare barrier:
         // the LDS reads still in flight (first value fragments of block b) read stages nobody overwrites yet.
         __builtin_amdgcn_s_barrier();
@@ -628,8 +641,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 if constexpr (gi < 4) {
                     // scores of block b+1 out of the MFMA result registers: elements 4 gi .. 4 gi + 3
                     // (the empty asm pins each copy to this point; otherwise the compiler sinks them all to their uses)
-                    if constexpr (slot == 1 || slot == 2) {
-                        constexpr int e0 = 4 * gi + 2 * (slot - 1);
+                    constexpr int first = GROUP_MFMAS >= 3 ? 1 : 0;   // the two slots that carry the fetch
+                    if constexpr (slot == first || slot == first + 1) {
+                        constexpr int e0 = 4 * gi + 2 * (slot - first);
                         sv[e0] = s[e0]; sv[e0 + 1] = s[e0 + 1]; tsv[e0] = ts[e0]; tsv[e0 + 1] = ts[e0 + 1];
                         asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]), "+v"(tsv[e0]), "+v"(tsv[e0 + 1]));
                     }
@@ -640,22 +654,27 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             accO[db] = VMFMA(vfr[gi % VRING], pb, accO[db]);
             behind(std::integral_constant<int, 0>{});
             FENCE();
-            accAB[db] = VMFMA(tvfr[gi % VRING], pb, accAB[db]);
-            behind(std::integral_constant<int, 1>{});
-            FENCE();
+            if constexpr (!ZT) {
+                accAB[db] = VMFMA(tvfr[gi % VRING], pb, accAB[db]);
+                behind(std::integral_constant<int, 1>{});
+                FENCE();
+            }
             accAB[db] = VMFMA(vfr[gi % VRING], hb8, accAB[db]);
-            behind(std::integral_constant<int, 2>{});
+            behind(std::integral_constant<int, PRODUCTS - 1>{});
             if constexpr (SPLIT) {
                 const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                 const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
                 FENCE();
                 accO[db] = VMFMA(vfr[gi % VRING], pl8, accO[db]);
-                behind(std::integral_constant<int, 3>{});
+                behind(std::integral_constant<int, PRODUCTS>{});
                 FENCE();
-                accAB[db] = VMFMA(tvfr[gi % VRING], pl8, accAB[db]);
-                behind(std::integral_constant<int, 4>{});
-                FENCE();
+                if constexpr (!ZT) {
+                    accAB[db] = VMFMA(tvfr[gi % VRING], pl8, accAB[db]);
+                    behind(std::integral_constant<int, PRODUCTS + 1>{});
+                    FENCE();
+                }
                 accAB[db] = VMFMA(vfr[gi % VRING], hl8, accAB[db]);
+                behind(std::integral_constant<int, 2 * PRODUCTS - 1>{});
             }
             FENCE();
             issue_copy_piece(FULLc, Gc, b);
@@ -809,8 +828,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
 }  // namespace
 
-// scale > 0: the kernel masks padded keys with a raw score of -inf and takes row maxima before scaling
-bool mfma_bf16_supports(const Problem& p) { return p.in_dtype == 0 && p.out_dtype == 0 && p.d == D && p.scale > 0.f; }
+// scale > 0: the kernel masks padded keys with a raw score of -inf and takes row maxima before scaling.
+// tk and tv are either both given or both absent (zero key/value tangents); single bf16 weights (FAST) are not built
+// for the latter.
+bool mfma_bf16_supports(const Problem& p) {
+    const bool zt = p.tk == nullptr && p.tv == nullptr;
+    return p.in_dtype == 0 && p.out_dtype == 0 && p.d == D && p.scale > 0.f && !(zt && (p.flags & 1));
+}
 
 hipError_t launch_mfma_bf16(const Problem& p) {
     if (!mfma_bf16_supports(p)) return hipErrorInvalidValue;
@@ -840,16 +864,23 @@ hipError_t launch_mfma_bf16(const Problem& p) {
     }
     MainKernelTimer timer(p);
     hipError_t e;
-    if (p.flags & 1) {
-        e = launch(attn_jvp_mfma_kernel<MODE_BF16>, p.v, p.tv, nullptr, nullptr);
+    if (p.tk == nullptr) {      // zero key/value tangents (the API admits them only as a pair)
+        if (f16) {
+            e = launch(attn_jvp_mfma_kernel<MODE_F16, true>, ws.v16, nullptr, ws.stats, ws.wg_flags);
+            if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, true>, p.v, nullptr, nullptr, ws.wg_flags);
+        } else {
+            e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, true>, p.v, nullptr, nullptr, nullptr);
+        }
+    } else if (p.flags & 1) {
+        e = launch(attn_jvp_mfma_kernel<MODE_BF16, false>, p.v, p.tv, nullptr, nullptr);
     } else if (f16) {
         // every tile is finished by exactly one of the two launches: the fp16 kernel flags the tiles it declines
         // (scores too spread out for fp16 weights) or abandons (overflow found at the end of its sweep), the
         // bf16-pair kernel does those and returns at once from the others
-        e = launch(attn_jvp_mfma_kernel<MODE_F16>, ws.v16, ws.tv16, ws.stats, ws.wg_flags);
-        if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT>, p.v, p.tv, nullptr, ws.wg_flags);
+        e = launch(attn_jvp_mfma_kernel<MODE_F16, false>, ws.v16, ws.tv16, ws.stats, ws.wg_flags);
+        if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, false>, p.v, p.tv, nullptr, ws.wg_flags);
     } else {
-        e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT>, p.v, p.tv, nullptr, nullptr);
+        e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, false>, p.v, p.tv, nullptr, nullptr);
     }
     return timer.finish(e);
 }

@@ -32,7 +32,7 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
     const int which = blockIdx.z;
     const int L = a.L[which];
     const int row0 = blockIdx.x * ROWS_PER_BLOCK;
-    if (row0 >= L) return;
+    if (row0 >= L || a.x[which] == nullptr) return;   // absent tangents leave their statistic at zero
     const long bh = blockIdx.y;
     const __hip_bfloat16* __restrict__ X = a.x[which] + bh * (long)L * D;
     const int sub = threadIdx.x & 15;            // 16 lanes x 16 B = one 256-byte row
@@ -77,16 +77,19 @@ __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat1
     const long base = bh * elems_per_head;
     for (long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < elems_per_head; i += (long)gridDim.x * blockDim.x * 8) {
         const uint4 a = *reinterpret_cast<const uint4*>(V + base + i);
-        const uint4 b = *reinterpret_cast<const uint4*>(tV + base + i);
-        const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
-        __half2 ao[4], bo[4];
+        const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+        __half2 ao[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            ao[j] = __floats2half2_rn(bf16_lo(aw[j]) * gV, bf16_hi(aw[j]) * gV);
-            bo[j] = __floats2half2_rn(bf16_lo(bw[j]) * gT, bf16_hi(bw[j]) * gT);
-        }
+        for (int j = 0; j < 4; ++j) ao[j] = __floats2half2_rn(bf16_lo(aw[j]) * gV, bf16_hi(aw[j]) * gV);
         *reinterpret_cast<uint4*>(V16 + base + i) = *reinterpret_cast<const uint4*>(ao);
-        *reinterpret_cast<uint4*>(tV16 + base + i) = *reinterpret_cast<const uint4*>(bo);
+        if (tV != nullptr) {                  // uniform: absent when the caller passes no key/value tangents
+            const uint4 b = *reinterpret_cast<const uint4*>(tV + base + i);
+            const uint32_t bw[4] = {b.x, b.y, b.z, b.w};
+            __half2 bo[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bo[j] = __floats2half2_rn(bf16_lo(bw[j]) * gT, bf16_hi(bw[j]) * gT);
+            *reinterpret_cast<uint4*>(tV16 + base + i) = *reinterpret_cast<const uint4*>(bo);
+        }
     }
 }
 

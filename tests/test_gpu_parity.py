@@ -254,6 +254,66 @@ def test_f16_path_abandons_tiles_that_overflow():
     assert (flags == 1).all()
 
 
+# ------------------------------------------------------------------ zero key/value tangents passed as NULL
+
+def run_gpu_no_kv_tangents(t, scale, kernel, flags=0):
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    o, to, lse = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], None, None, scale,
+                                         kernel=kernel, flags=flags)
+    torch.cuda.synchronize()
+    return o.cpu().double().numpy(), to.cpu().double().numpy(), lse.cpu().double().numpy()
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+@pytest.mark.parametrize("Lq,Lkv", [(2, 3), (130, 65), (200, 512), (260, 4100)])
+def test_mfma_null_kv_tangents_equal_explicit_zeros(variant, Lq, Lkv):
+    """tk = tv = NULL runs 4 of the 6 products and streams only K, V; adding the products with zero operands changes
+    no bit of an fp32 accumulator, so the result must be IDENTICAL to the call with zero tensors, and match the oracle."""
+    t = random_inputs(700 + Lq + Lkv, 1, 2, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
+    t["tk"].zero_(); t["tv"].zero_()
+    scale = 128 ** -0.5
+    zeros = run_gpu(t, scale, binding.KERNEL_MFMA, VARIANTS[variant])
+    null = run_gpu_no_kv_tangents(t, scale, binding.KERNEL_MFMA, VARIANTS[variant])
+    for a, b, name in zip(null, zeros, ("o", "to", "lse")):
+        np.testing.assert_array_equal(a, b, err_msg=f"{name} differs between NULL and zero key/value tangents")
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    compare(null, ref, torch.bfloat16, f"mfma {variant} tk=tv=NULL Lq={Lq} Lkv={Lkv}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_vector_kernel_null_kv_tangents(dtype):
+    t = random_inputs(77, 1, 2, 100, 77, 64, dtype, tangent_std=1.0)
+    t["tk"].zero_(); t["tv"].zero_()
+    zeros = run_gpu(t, 0.125, binding.KERNEL_FP32)
+    null = run_gpu_no_kv_tangents(t, 0.125, binding.KERNEL_FP32)
+    for a, b in zip(null, zeros):
+        np.testing.assert_array_equal(a, b)
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], 0.125)
+    compare(null, ref, dtype, f"vector kernel tk=tv=NULL {dtype}")
+
+
+def test_null_kv_tangents_argument_rules():
+    t = random_inputs(78, 1, 1, 64, 64, 128, torch.bfloat16)
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    with pytest.raises(ValueError):            # the binding wants both or neither
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], None, dev["tv"], 0.1)
+    with pytest.raises(binding.AttnJvpError):  # single-bf16 weights are not built without key/value tangents
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], None, None, 0.1,
+                                kernel=binding.KERNEL_MFMA, flags=binding.FLAG_FAST)
+
+
+def test_config4_null_kv_tangents_default_path():
+    """The cross-attention configuration with its zero tangents not passed at all, default launch configuration."""
+    cfg = CONFIGS[4]
+    t = make_inputs(cfg)
+    got = run_gpu_no_kv_tangents(t, cfg.scale, binding.KERNEL_AUTO)
+    rows = sample_rows(cfg, 512)
+    for h in range(cfg.H):
+        sl = lambda x: x[:, h:h + 1]
+        ref = attn_jvp_ref(sl(t["q"]), sl(t["k"]), sl(t["v"]), sl(t["tq"]), sl(t["tk"]), sl(t["tv"]), cfg.scale, rows=rows)
+        compare(tuple(x[:, h:h + 1] for x in got), ref, cfg.torch_dtype, f"cfg4 tk=tv=NULL h{h}", rows=rows)
+
+
 # ------------------------------------------------------------------ the five named configurations
 
 def check_config_sampled(cfg, n_random, heads=None):

@@ -82,6 +82,8 @@ def test_argument_validation_returns_codes_without_launching(lib):
     for i in range(9):
         p = list(good); p[i] = 0
         assert _call(lib, p) == 1                         # NULL_PTR
+    p = list(good); p[4] = 0; p[5] = 0                    # tk = tv = NULL is legal: the next check decides
+    assert _call(lib, p, dims=(1, 1, 8, 8, 48)) == 3      # ... here the unsupported head dim
     for i in range(5):
         for bad in (0, -3):
             dims = [1, 1, 8, 8, 128]; dims[i] = bad
