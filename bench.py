@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--null-kv-tangents", action="store_true",
                     help="pass tk = tv = NULL instead of the tensors (only meaningful where they are zero: config 4); "
                          "the kernel then executes 8*Lq*Lkv*d flop per head, the metric still counts 12")
+    ap.add_argument("--layout", choices=["bhld", "blhd"], default="bhld",
+                    help="memory layout of the eight tensors: [B,H,L,d] (default) or [B,L,H,d]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (known traffic) for scaling HBM counters")
@@ -66,7 +68,11 @@ def main():
     torch.cuda.set_device(dev)
     t = {n: x.to(dev) for n, x in make_inputs(cfg).items()}
     B, H, Lq, Lkv, d = cfg.B, cfg.H, cfg.Lq, cfg.Lkv, cfg.d
-    o = torch.empty(B, H, Lq, d, dtype=torch.float32, device=dev)
+    layout = binding.LAYOUT_BHLD
+    if args.layout == "blhd":
+        t = {n: x.permute(0, 2, 1, 3).contiguous() for n, x in t.items()}
+        layout = binding.LAYOUT_BLHD
+    o = torch.empty(t["q"].shape, dtype=torch.float32, device=dev)
     to = torch.empty_like(o)
     lse = torch.empty(B, H, Lq, dtype=torch.float32, device=dev)
     if args.fast:
@@ -80,7 +86,7 @@ def main():
 
     def step(events=None):
         binding.attn_jvp_fwd_ex(t["q"], t["k"], t["v"], t["tq"], tk, tv, cfg.scale, out=(o, to, lse),
-                                flags=flags, timing_events=events)
+                                flags=flags, timing_events=events, layout=layout)
 
     for _ in range(args.warmup):
         step()
@@ -116,7 +122,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
-                   "variant": args.variant, "kv_tangents": "null" if args.null_kv_tangents else "tensors"},
+                   "variant": args.variant, "kv_tangents": "null" if args.null_kv_tangents else "tensors", "layout": args.layout},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,

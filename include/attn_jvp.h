@@ -18,9 +18,9 @@
  * nothing and keeps no state between calls.  It needs no workspace; if the caller lends one
  * (attn_jvp_opts.workspace, see attn_jvp_workspace_bytes) the bf16 kernel uses its faster
  * fp16-value path.
- *   q, tq        [B, H, Lq,  d]  contiguous, row-major, d fastest
+ *   q, tq        [B, H, Lq,  d]  contiguous, row-major, d fastest (or [B, Lq, H, d], see attn_jvp_opts.layout)
  *   k, v, tk, tv [B, H, Lkv, d]  same
- *   o, to        [B, H, Lq,  d]  float32 (or the input dtype, see attn_jvp_opts.out_dtype)
+ *   o, to        [B, H, Lq,  d]  float32 (or the input dtype, see attn_jvp_opts.out_dtype), same layout as q
  *   lse          [B, H, Lq]      float32, natural log
  * Inputs are never written.  Outputs must not alias inputs or one another.  All pointers
  * must be 16-byte aligned.
@@ -57,6 +57,12 @@ extern "C" {
 #define ATTN_JVP_FP32 1
 #define ATTN_JVP_OUT_FP32  0      /* o, to are float32 (default; the accumulators' own precision) */
 #define ATTN_JVP_OUT_INPUT 1      /* o, to have the input dtype */
+
+/* attn_jvp_opts.layout */
+#define ATTN_JVP_LAYOUT_BHLD 0    /* [B, H, L, d] (default) */
+#define ATTN_JVP_LAYOUT_BLHD 1    /* [B, L, H, d]: what a sequence-to-head all-to-all (Ulysses context parallelism,
+                                     paper Sec. 3.2) leaves on each GPU, consumed and produced without a transpose.
+                                     lse stays [B, H, Lq]. */
 
 /* attn_jvp_opts.kernel */
 #define ATTN_JVP_KERNEL_AUTO 0    /* bf16, d=128, scale > 0 -> MFMA kernel; everything else -> fp32 vector kernel */
@@ -95,7 +101,8 @@ typedef struct attn_jvp_opts {
                                [0] is recorded on `stream` immediately before the main attention kernel and [1]
                                immediately after it, so a profiler can time that kernel apart from the fp16
                                path's pre-pass kernels, which are enqueued before [0] */
-    int    reserved[2];     /* must be zero */
+    int    layout;          /* ATTN_JVP_LAYOUT_*: memory layout of q, k, v, tq, tk, tv, o, to */
+    int    reserved;        /* must be zero */
 } attn_jvp_opts;
 
 /*

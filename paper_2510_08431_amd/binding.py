@@ -13,6 +13,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libattn_jvp.so")
 
 KERNEL_AUTO, KERNEL_FP32, KERNEL_MFMA = 0, 1, 2
+LAYOUT_BHLD = 0   # tensors are [B, H, L, d]
+LAYOUT_BLHD = 1   # tensors are [B, L, H, d] (lse stays [B, H, Lq])
 FLAG_FAST = 1     # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key block; not tolerance-safe)
 FLAG_F16_ALWAYS = 4   # MFMA kernel: fp16 value path also for Lkv < 2048 (given a workspace)
 FLAG_NO_F16 = 2   # MFMA kernel: hi + lo bf16 pairs (9 products) even when a workspace is available
@@ -23,7 +25,7 @@ class AttnJvpOpts(ctypes.Structure):
     _fields_ = [("in_dtype", ctypes.c_int), ("out_dtype", ctypes.c_int), ("stream", ctypes.c_void_p),
                 ("kernel", ctypes.c_int), ("flags", ctypes.c_int), ("workspace", ctypes.c_void_p),
                 ("workspace_bytes", ctypes.c_size_t), ("timing_events", ctypes.c_void_p * 2),
-                ("reserved", ctypes.c_int * 2)]
+                ("layout", ctypes.c_int), ("reserved", ctypes.c_int)]
 
 
 class AttnJvpError(RuntimeError):
@@ -91,22 +93,30 @@ def _ptr(t):
     return t.data_ptr() if t is not None else None
 
 
-def _check_inputs(q, k, v, tq, tk, tv):
-    if q.dim() != 4:
-        raise ValueError("q must be [B, H, Lq, d]")
-    B, H, Lq, d = q.shape
-    Lkv = k.shape[2]
+def _check_inputs(q, k, v, tq, tk, tv, layout=LAYOUT_BHLD):
+    if q.dim() != 4 or k.dim() != 4:
+        raise ValueError("q and k must be [B, H, L, d] (or [B, L, H, d] with layout=LAYOUT_BLHD)")
+    if layout == LAYOUT_BLHD:
+        B, Lq, H, d = q.shape
+        Lkv = k.shape[1]
+        shape = lambda L: (B, L, H, d)
+    elif layout == LAYOUT_BHLD:
+        B, H, Lq, d = q.shape
+        Lkv = k.shape[2]
+        shape = lambda L: (B, H, L, d)
+    else:
+        raise ValueError(f"unknown layout {layout}")
     if (tk is None) != (tv is None):
         raise ValueError("tk and tv must both be given or both be None (zero key/value tangents)")
     for name, t, L in (("q", q, Lq), ("tq", tq, Lq), ("k", k, Lkv), ("v", v, Lkv), ("tk", tk, Lkv), ("tv", tv, Lkv)):
         if t is None:
             continue
-        if tuple(t.shape) != (B, H, L, d):
-            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {(B, H, L, d)}")
+        if tuple(t.shape) != shape(L):
+            raise ValueError(f"{name} has shape {tuple(t.shape)}, expected {shape(L)}")
         if t.dtype != q.dtype or t.device != q.device:
             raise ValueError(f"{name}: dtype/device differ from q")
         if not t.is_contiguous():
-            raise ValueError(f"{name} must be contiguous [B, H, L, d]")
+            raise ValueError(f"{name} must be contiguous")
     if q.dtype not in _DTYPE_CODE:
         raise ValueError(f"unsupported dtype {q.dtype}")
     if not q.is_cuda:
@@ -115,25 +125,28 @@ def _check_inputs(q, k, v, tq, tk, tv):
 
 
 def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float32, kernel=KERNEL_AUTO, stream=None,
-                    flags=0, workspace="auto", timing_events=None):
+                    flags=0, workspace="auto", timing_events=None, layout=LAYOUT_BHLD):
     """Enqueue O, tO, lse = attention forward + JVP on the current (or given) stream.
 
     q, tq: [B, H, Lq, d]; k, v, tk, tv: [B, H, Lkv, d]; bf16 or fp32, contiguous, on the GPU.  tk and tv may both be
     None: zero key/value tangents (cross-attention onto a context without tangent).
     out: optional (o, to, lse) to write into.  workspace: "auto" (a cached per-device torch buffer), None (no
-    scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  timing_events: optional pair of
+    scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  layout=LAYOUT_BLHD: all eight
+    tensors are [B, L, H, d] instead (lse stays [B, H, Lq]).  timing_events: optional pair of
     torch.cuda.Event(enable_timing=True) that the library records right before and after the main kernel.
     Returns (o, to, lse); asynchronous.
     """
     lib = load_library()
-    B, H, Lq, Lkv, d = _check_inputs(q, k, v, tq, tk, tv)
+    B, H, Lq, Lkv, d = _check_inputs(q, k, v, tq, tk, tv, layout)
     if out is None:
-        o = torch.empty(B, H, Lq, d, dtype=out_dtype, device=q.device)
+        o = torch.empty(q.shape, dtype=out_dtype, device=q.device)     # same layout as q
         to = torch.empty_like(o)
         lse = torch.empty(B, H, Lq, dtype=torch.float32, device=q.device)
     else:
         o, to, lse = out
         out_dtype = o.dtype
+        if tuple(o.shape) != tuple(q.shape) or tuple(to.shape) != tuple(q.shape) or tuple(lse.shape) != (B, H, Lq):
+            raise ValueError("out must be (o, to, lse) with o, to shaped like q and lse [B, H, Lq]")
     if out_dtype not in (torch.float32, q.dtype):
         raise ValueError("out_dtype must be float32 or the input dtype")
     opts = AttnJvpOpts()
@@ -144,6 +157,7 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     opts.stream = stream.cuda_stream
     opts.kernel = int(kernel)
     opts.flags = int(flags)
+    opts.layout = int(layout)
     if isinstance(workspace, str) and workspace == "auto":
         need = lib.attn_jvp_workspace_bytes(B, H, Lq, Lkv, d) if q.dtype == torch.bfloat16 else 0
         workspace = _workspace(q.device, need) if need else None

@@ -27,8 +27,8 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     if (elems > 4.0e18L || (long long)B * H > 0x7fffffffLL) return ATTN_JVP_BAD_SHAPE;
     if (opts->in_dtype != ATTN_JVP_BF16 && opts->in_dtype != ATTN_JVP_FP32) return ATTN_JVP_UNSUPPORTED;
     if (opts->out_dtype != ATTN_JVP_OUT_FP32 && opts->out_dtype != ATTN_JVP_OUT_INPUT) return ATTN_JVP_UNSUPPORTED;
-    for (int i = 0; i < 2; ++i)
-        if (opts->reserved[i] != 0) return ATTN_JVP_UNSUPPORTED;
+    if (opts->layout != ATTN_JVP_LAYOUT_BHLD && opts->layout != ATTN_JVP_LAYOUT_BLHD) return ATTN_JVP_UNSUPPORTED;
+    if (opts->reserved != 0) return ATTN_JVP_UNSUPPORTED;
     if (opts->flags & ~(ATTN_JVP_FLAG_FAST | ATTN_JVP_FLAG_NO_F16 | ATTN_JVP_FLAG_F16_ALWAYS)) return ATTN_JVP_UNSUPPORTED;
     if (opts->workspace && (reinterpret_cast<uintptr_t>(opts->workspace) & 255u)) return ATTN_JVP_MISALIGNED;
     const void* ptrs[] = {q, k, v, tq, tk, tv, o, to, lse};
@@ -38,7 +38,8 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     Problem p{q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale,
               opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags,
               opts->workspace, opts->workspace ? opts->workspace_bytes : 0,
-              static_cast<hipEvent_t>(opts->timing_events[0]), static_cast<hipEvent_t>(opts->timing_events[1])};
+              static_cast<hipEvent_t>(opts->timing_events[0]), static_cast<hipEvent_t>(opts->timing_events[1]),
+              opts->layout};
 
     int kernel = opts->kernel;
     if (kernel == ATTN_JVP_KERNEL_AUTO)

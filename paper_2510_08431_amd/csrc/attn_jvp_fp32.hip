@@ -48,7 +48,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
     const TIn* __restrict__ Q, const TIn* __restrict__ K, const TIn* __restrict__ V,
     const TIn* __restrict__ tQ, const TIn* __restrict__ tK, const TIn* __restrict__ tV,
     TOut* __restrict__ O, TOut* __restrict__ tO, float* __restrict__ LSE,
-    int Lq, int Lkv, float scale) {
+    int Lq, int Lkv, float scale, int H, int blhd) {
     constexpr int NCH = D / 16;                 // float4 chunks per lane
     extern __shared__ float4 smem[];            // 4 tiles of BC x D floats
     float4* sK = smem;
@@ -64,12 +64,17 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
     const int qrow = q0 + row_in_blk;
     const int qrow_ld = qrow < Lq ? qrow : Lq - 1;          // ragged last block: duplicate a valid row, never stored
 
-    const TIn* Qb = Q + (bh * Lq + qrow_ld) * D;
-    const TIn* tQb = tQ + (bh * Lq + qrow_ld) * D;
-    const TIn* Kb = K + bh * (long)Lkv * D;
-    const TIn* tKb = tK + bh * (long)Lkv * D;
-    const TIn* Vb = V + bh * (long)Lkv * D;
-    const TIn* tVb = tV + bh * (long)Lkv * D;
+    // [B,H,L,d]: rows of a head contiguous; [B,L,H,d]: rows of a head H*d elements apart
+    const int row_elems = blhd ? H * D : D;
+    const long bidx = bh / H, hidx = bh % H;
+    const long q_base = blhd ? (bidx * Lq * H + hidx) * D : bh * (long)Lq * D;
+    const long kv_base = blhd ? (bidx * Lkv * H + hidx) * D : bh * (long)Lkv * D;
+    const TIn* Qb = Q + q_base + (long)qrow_ld * row_elems;
+    const TIn* tQb = tQ + q_base + (long)qrow_ld * row_elems;
+    const TIn* Kb = K + kv_base;
+    const TIn* tKb = tK + kv_base;
+    const TIn* Vb = V + kv_base;
+    const TIn* tVb = tV + kv_base;
 
     float4 q[NCH], tq[NCH], acc_o[NCH], acc_ab[NCH];
 #pragma unroll
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
             int rr = idx / (D / 4), cc = idx % (D / 4);
             int krow = j0 + rr;
             krow = krow < Lkv ? krow : Lkv - 1;  // pad rows duplicate the last key; masked below
-            long off = (long)krow * D + 4 * cc;
+            long off = (long)krow * row_elems + 4 * cc;
             sK[idx] = Ld<TIn>::load4(Kb + off);
             stK[idx] = tK ? Ld<TIn>::load4(tKb + off) : make_float4(0.f, 0.f, 0.f, 0.f);   // absent tangents are zero
             sV[idx] = Ld<TIn>::load4(Vb + off);
@@ -149,8 +154,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
     if (qrow < Lq) {
         const float inv_l = 1.f / l;
         const float mu = r * inv_l;             // rowsum(P o tS)
-        TOut* Ob = O + (bh * Lq + qrow) * D;
-        TOut* tOb = tO + (bh * Lq + qrow) * D;
+        TOut* Ob = O + q_base + (long)qrow * row_elems;
+        TOut* tOb = tO + q_base + (long)qrow * row_elems;
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             float4 o4 = acc_o[c], ab = acc_ab[c], t4;
@@ -176,7 +181,7 @@ hipError_t launch_one(const Problem& p) {
     hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), smem, p.stream,
                        (const TIn*)p.q, (const TIn*)p.k, (const TIn*)p.v,
                        (const TIn*)p.tq, (const TIn*)p.tk, (const TIn*)p.tv,
-                       (TOut*)p.o, (TOut*)p.to, p.lse, p.Lq, p.Lkv, p.scale);
+                       (TOut*)p.o, (TOut*)p.to, p.lse, p.Lq, p.Lkv, p.scale, p.H, p.layout);
     return timer.finish(hipGetLastError());
 }
 

@@ -140,7 +140,7 @@ __device__ __forceinline__ void load_lds_b128(const void* uniform_base, uint32_t
 // reads); V, tV (VSWZ): chunk ^= (row & 3) << 2 (transposing b64 reads).  Rows past Lkv re-read the last valid
 // row (finite values; their scores are masked to -inf).
 template <bool VSWZ, bool WITH_TANGENT>
-__device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* tXh, int j0, int Lkv,
+__device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* tXh, long row_stride, int j0, int Lkv,
                                                    uint32_t stage_base, int wave, int lane) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -149,7 +149,7 @@ __device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* t
         const int pc = lane & 15;
         int grow = j0 + row;
         grow = grow < Lkv ? grow : Lkv - 1;
-        const long goff = (long)grow * ROW_BYTES + ((VSWZ ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15))) << 4);
+        const long goff = (long)grow * row_stride + ((VSWZ ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15))) << 4);
         const uint32_t dst = stage_base + rowblk * 1024;
         ATTN_JVP_LOAD_LDS(Xh + goff, dst);
         if constexpr (WITH_TANGENT) ATTN_JVP_LOAD_LDS(tXh + goff, dst + TENSOR_BYTES);
@@ -158,14 +158,14 @@ __device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* t
 // Same copy for a block known to lie entirely inside the sequence: the per-lane byte offsets (row and swizzled
 // chunk) never change, so they are computed once and only the uniform block base advances.
 struct LaneOffsets { uint32_t k[2], v[2]; };
-__device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane) {
+__device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int k_stride, int v_stride) {
     LaneOffsets o;
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
         const int row = (wave * 2 + i) * 4 + (lane >> 4);
         const int pc = lane & 15;
-        o.k[i] = row * ROW_BYTES + ((pc ^ (row & 15)) << 4);
-        o.v[i] = row * ROW_BYTES + ((pc ^ ((row & 3) << 2)) << 4);
+        o.k[i] = row * k_stride + ((pc ^ (row & 15)) << 4);
+        o.v[i] = row * v_stride + ((pc ^ ((row & 3) << 2)) << 4);
     }
     return o;
 }
@@ -187,7 +187,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     float* __restrict__ O, float* __restrict__ tO, float* __restrict__ LSE,
-    int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags) {
+    int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
+    int H, int blhd) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16;
     // Hand-over between the fp16 launch and the bf16-pair launch that follows it on the same stream: the fp16
@@ -207,18 +208,28 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const long bh = bid / q_tiles;
     const int q0 = (bid % q_tiles) * BR + wave * 32;
 
-    const char* Kh = reinterpret_cast<const char*>(K) + bh * (long)Lkv * ROW_BYTES;
-    const char* tKh = reinterpret_cast<const char*>(tK) + bh * (long)Lkv * ROW_BYTES;
-    const char* Vh = static_cast<const char*>(V) + bh * (long)Lkv * ROW_BYTES;      // bf16, or the fp16 copies
-    const char* tVh = static_cast<const char*>(tV) + bh * (long)Lkv * ROW_BYTES;
+    // Memory layout of the caller's tensors: [B,H,L,d] (rows of a head contiguous) or [B,L,H,d] (rows of a head H*d
+    // apart).  Element offset of row r of head (b, h): head_base + r * row_elems.  The fp16 copies of V, tV in the
+    // workspace are always [B,H,L,d].
+    const int row_elems = blhd ? H * D : D;
+    const long bidx = bh / H, hidx = bh % H;
+    const long q_base = blhd ? (bidx * Lq * H + hidx) * D : bh * (long)Lq * D;
+    const long kv_base = blhd ? (bidx * Lkv * H + hidx) * D : bh * (long)Lkv * D;
+    const int k_stride = row_elems * 2;                                  // bytes between key rows
+    const int v_stride = F16 ? ROW_BYTES : k_stride;
+    const long v_base = F16 ? bh * (long)Lkv * D : kv_base;
+    const char* Kh = reinterpret_cast<const char*>(K) + kv_base * 2;
+    const char* tKh = reinterpret_cast<const char*>(tK) + kv_base * 2;
+    const char* Vh = static_cast<const char*>(V) + v_base * 2;           // bf16, or the fp16 copies
+    const char* tVh = static_cast<const char*>(tV) + v_base * 2;
     const int n_blocks = (Lkv + BC - 1) / BC;
 
     // block x: K|tK in K-ring stage x & 3, V|tV in V-ring stage x & 3
     auto copy_k = [&](int blk) __attribute__((always_inline)) {
-        issue_pair_clamped<false, !ZT>(Kh, tKh, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
+        issue_pair_clamped<false, !ZT>(Kh, tKh, k_stride, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
     auto copy_v = [&](int blk) __attribute__((always_inline)) {
-        issue_pair_clamped<true, !ZT>(Vh, tVh, blk * BC, Lkv,
+        issue_pair_clamped<true, !ZT>(Vh, tVh, v_stride, blk * BC, Lkv,
                                       lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
     // start the rings while Q is being fetched (rows past the end are clamped, so all copies are unconditional);
@@ -243,7 +254,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 const int pc = lane & 15;
                 int grow = blk * BC + row;
                 grow = grow < Lkv ? grow : Lkv - 1;
-                ATTN_JVP_LOAD_LDS(Kh + (long)grow * ROW_BYTES + ((pc ^ (row & 15)) << 4),
+                ATTN_JVP_LOAD_LDS(Kh + (long)grow * k_stride + ((pc ^ (row & 15)) << 4),
                                   lds0 + (uint32_t)i * TENSOR_BYTES + rowblk * 1024);
             }
         }
@@ -256,8 +267,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const int qrow_ld = qrow < Lq ? qrow : Lq - 1;
     bf16x8 qf[8], tqf[8];
     {
-        const bf16x8* qp = reinterpret_cast<const bf16x8*>(Q + (bh * Lq + qrow_ld) * D + 8 * g);
-        const bf16x8* tqp = reinterpret_cast<const bf16x8*>(tQ + (bh * Lq + qrow_ld) * D + 8 * g);
+        const bf16x8* qp = reinterpret_cast<const bf16x8*>(Q + q_base + (long)qrow_ld * row_elems + 8 * g);
+        const bf16x8* tqp = reinterpret_cast<const bf16x8*>(tQ + q_base + (long)qrow_ld * row_elems + 8 * g);
 #pragma unroll
         for (int t = 0; t < 8; ++t) { qf[t] = qp[2 * t]; tqf[t] = tqp[2 * t]; }
 #pragma unroll
@@ -535,7 +546,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // groups ahead inside their own phase, through small register rings.
     constexpr int KPRE = 3, KRING = KPRE + 1, VPRE = 2, VRING = VPRE + 1;
     constexpr int KFIRST = 2;   // value group after which the next iteration's first score fragments are requested
-    const LaneOffsets lofs = make_lane_offsets(wave, lane);
+    const LaneOffsets lofs = make_lane_offsets(wave, lane, k_stride, v_stride);
     const int n_full = Lkv / BC;                       // blocks that need no row clamping
     bf16x8 kfr[KRING], tkfr[KRING], vfr[VRING], tvfr[VRING];
     auto read_k = [&](auto T, auto ST) __attribute__((always_inline)) {     // score step T of the block in K stage ST
@@ -568,14 +579,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                              (which & 1) * TENSOR_BYTES + (wave * 2 + i) * 1024;
         if constexpr (decltype(FULLc)::value) {
             const uint32_t lo = which < 2 ? lofs.k[i] : lofs.v[i];
-            load_lds_b128(base + (long)blk * (BC * ROW_BYTES), lo, __builtin_amdgcn_readfirstlane(dst));
+            load_lds_b128(base + (long)blk * (BC * (which < 2 ? k_stride : v_stride)), lo, __builtin_amdgcn_readfirstlane(dst));
         } else {
             const int row = (wave * 2 + i) * 4 + (lane >> 4);
             const int pc = lane & 15;
             int grow = blk * BC + row;
             grow = grow < Lkv ? grow : Lkv - 1;
             const int chunk = which < 2 ? (pc ^ (row & 15)) : (pc ^ ((row & 3) << 2));
-            ATTN_JVP_LOAD_LDS(base + (long)grow * ROW_BYTES + (chunk << 4), dst);
+            ATTN_JVP_LOAD_LDS(base + (long)grow * (which < 2 ? k_stride : v_stride) + (chunk << 4), dst);
         }
     };
 
@@ -804,8 +815,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const float mu = r_row * inv_l;
     const float fo = gO * inv_l, ft = gAB * inv_l;
     if (qrow < Lq) {
-        float* Op = O + (bh * Lq + qrow) * D + 4 * g;
-        float* tOp = tO + (bh * Lq + qrow) * D + 4 * g;
+        float* Op = O + q_base + (long)qrow * row_elems + 4 * g;
+        float* tOp = tO + q_base + (long)qrow * row_elems + 4 * g;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -848,7 +859,7 @@ hipError_t launch_mfma_bf16(const Problem& p) {
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
-                           (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags);
+                           (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout);
         return hipGetLastError();
     };
     // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence

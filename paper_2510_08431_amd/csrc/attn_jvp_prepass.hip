@@ -24,7 +24,13 @@ __global__ void zero_stats_kernel(float* stats, int n) {
 struct StatsArgs {
     const __hip_bfloat16* x[6];   // V, tV, Q, tQ, K, tK
     int L[6];
+    int H, blhd;                  // layout of the tensors: [B,H,L,d] or [B,L,H,d]
 };
+
+// element offset of row `row` of head `bh` in a tensor with L rows per head
+__device__ __forceinline__ long row_offset(long bh, int row, int L, int H, int blhd) {
+    return blhd ? (((bh / H) * L + row) * H + bh % H) * (long)D : (bh * L + row) * (long)D;
+}
 
 // One launch for all six tensors: blockIdx.z selects the tensor.  Slot 0, 1: abs max of V, tV; slots 2..5: largest
 // squared row norm of Q, tQ, K, tK.
@@ -34,7 +40,7 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
     const int row0 = blockIdx.x * ROWS_PER_BLOCK;
     if (row0 >= L || a.x[which] == nullptr) return;   // absent tangents leave their statistic at zero
     const long bh = blockIdx.y;
-    const __hip_bfloat16* __restrict__ X = a.x[which] + bh * (long)L * D;
+    const __hip_bfloat16* __restrict__ X = a.x[which];
     const int sub = threadIdx.x & 15;            // 16 lanes x 16 B = one 256-byte row
     const int r_in = threadIdx.x >> 4;
     float best = 0.f;
@@ -43,7 +49,8 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
 #pragma unroll
         for (int u = 0; u < 4; ++u) {            // four independent 16-byte loads in flight per lane
             const int row = row0 + rr + 16 * u;
-            w[u] = row < L ? *reinterpret_cast<const uint4*>(X + (long)row * D + sub * 8) : make_uint4(0, 0, 0, 0);
+            w[u] = row < L ? *reinterpret_cast<const uint4*>(X + row_offset(bh, row, L, a.H, a.blhd) + sub * 8)
+                           : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -70,20 +77,23 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
 __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat16* __restrict__ V,
                                                              const __hip_bfloat16* __restrict__ tV,
                                                              const float* __restrict__ stats, __half* __restrict__ V16,
-                                                             __half* __restrict__ tV16, long elems_per_head, float scale) {
+                                                             __half* __restrict__ tV16, long elems_per_head, float scale,
+                                                             int Lkv, int H, int blhd) {
     const long bh = blockIdx.y;
     const F16Scales sc = f16_scales(stats + bh * 8, scale);
     const float gV = ldexpf(1.f, -sc.eV), gT = ldexpf(1.f, -sc.eA);
     const long base = bh * elems_per_head;
     for (long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < elems_per_head; i += (long)gridDim.x * blockDim.x * 8) {
-        const uint4 a = *reinterpret_cast<const uint4*>(V + base + i);
+        // i indexes the head's rows in [L,d] order (the order of the fp16 copies); the source row may be strided
+        const long src = row_offset(bh, (int)(i / D), Lkv, H, blhd) + i % D;
+        const uint4 a = *reinterpret_cast<const uint4*>(V + src);
         const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
         __half2 ao[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) ao[j] = __floats2half2_rn(bf16_lo(aw[j]) * gV, bf16_hi(aw[j]) * gV);
         *reinterpret_cast<uint4*>(V16 + base + i) = *reinterpret_cast<const uint4*>(ao);
         if (tV != nullptr) {                  // uniform: absent when the caller passes no key/value tangents
-            const uint4 b = *reinterpret_cast<const uint4*>(tV + base + i);
+            const uint4 b = *reinterpret_cast<const uint4*>(tV + src);
             const uint32_t bw[4] = {b.x, b.y, b.z, b.w};
             __half2 bo[4];
 #pragma unroll
@@ -128,6 +138,8 @@ hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out) {
         sa.x[i] = static_cast<const __hip_bfloat16*>(xs[i]);
         sa.L[i] = (i == 2 || i == 3) ? p.Lq : p.Lkv;
     }
+    sa.H = p.H;
+    sa.blhd = p.layout;
     const int Lmax = p.Lq > p.Lkv ? p.Lq : p.Lkv;
     auto bf = [](const void* x) { return static_cast<const __hip_bfloat16*>(x); };
     hipLaunchKernelGGL(head_stats_kernel, dim3((Lmax + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, (unsigned)heads, 6), dim3(256), 0,
@@ -137,7 +149,7 @@ hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out) {
     if (cx > 512) cx = 512;
     if (cx < 1) cx = 1;
     hipLaunchKernelGGL(convert_values_kernel, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), stats,
-                       V16, tV16, eph, p.scale);
+                       V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
     out->stats = stats;
     out->wg_flags = wg_flags;
     out->v16 = V16;

@@ -18,6 +18,7 @@ struct Problem {
     void* workspace;        // optional device scratch for the fp16 value path (may be null)
     size_t workspace_bytes;
     hipEvent_t ev_start, ev_stop;   // optional: recorded around the main kernel (may be null)
+    int layout;     // 0: q, k, v, tq, tk, tv, o, to are [B,H,L,d]; 1: they are [B,L,H,d].  lse is [B,H,Lq] either way
 };
 
 // Records the caller's optional timing events around the main kernel's launch.

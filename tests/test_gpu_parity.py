@@ -314,6 +314,57 @@ def test_config4_null_kv_tangents_default_path():
         compare(tuple(x[:, h:h + 1] for x in got), ref, cfg.torch_dtype, f"cfg4 tk=tv=NULL h{h}", rows=rows)
 
 
+# ------------------------------------------------------------------ [B, L, H, d] layout
+
+def run_gpu_blhd(t, scale, kernel, flags=0, null_kv=False):
+    """Same call with every tensor handed over as [B, L, H, d]; outputs permuted back to [B, H, L, d]."""
+    dev = {n: x.to(DEV).permute(0, 2, 1, 3).contiguous() for n, x in t.items()}
+    tk, tv = (None, None) if null_kv else (dev["tk"], dev["tv"])
+    o, to, lse = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], tk, tv, scale,
+                                         kernel=kernel, flags=flags, layout=binding.LAYOUT_BLHD)
+    torch.cuda.synchronize()
+    assert tuple(o.shape) == tuple(dev["q"].shape) and tuple(lse.shape) == (o.shape[0], o.shape[2], o.shape[1])
+    back = lambda x: x.permute(0, 2, 1, 3).contiguous().cpu().double().numpy()
+    return back(o), back(to), lse.cpu().double().numpy()
+
+
+@pytest.mark.parametrize("case", ["f16", "bf16-pairs", "fast", "f16-null-kv", "pairs-null-kv", "vector-fp32", "vector-bf16",
+                                  "default-long"])
+def test_blhd_layout_gives_the_same_bits(case):
+    """[B, L, H, d] tensors (what a sequence-to-head all-to-all leaves behind) go through the same arithmetic in the
+    same order as [B, H, L, d]: every output bit must agree, for every kernel variant; plus oracle parity once."""
+    B, H, Lq, Lkv, d, dtype, kernel, flags, null_kv = 2, 3, 200, 333, 128, torch.bfloat16, binding.KERNEL_MFMA, 0, False
+    if case == "f16":
+        flags = binding.FLAG_F16_ALWAYS
+    elif case == "bf16-pairs":
+        flags = binding.FLAG_NO_F16
+    elif case == "fast":
+        flags = binding.FLAG_FAST
+    elif case == "f16-null-kv":
+        flags, null_kv = binding.FLAG_F16_ALWAYS, True
+    elif case == "pairs-null-kv":
+        flags, null_kv = binding.FLAG_NO_F16, True
+    elif case == "vector-fp32":
+        d, dtype, kernel = 64, torch.float32, binding.KERNEL_FP32
+    elif case == "vector-bf16":
+        d, kernel = 64, binding.KERNEL_FP32
+    elif case == "default-long":
+        B, H, Lq, Lkv, kernel = 1, 2, 260, 4100, binding.KERNEL_AUTO
+    t = random_inputs(900 + len(case), B, H, Lq, Lkv, d, dtype)
+    if null_kv:
+        t["tk"].zero_(); t["tv"].zero_()
+    scale = d ** -0.5
+    if null_kv:
+        bhld = run_gpu_no_kv_tangents(t, scale, kernel, flags)
+    else:
+        bhld = run_gpu(t, scale, kernel, flags)
+    blhd = run_gpu_blhd(t, scale, kernel, flags, null_kv)
+    for a, b, name in zip(blhd, bhld, ("o", "to", "lse")):
+        np.testing.assert_array_equal(a, b, err_msg=f"{case}: {name} differs between the two layouts")
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    compare(blhd, ref, dtype, f"[B,L,H,d] {case}", tol=FAST_TOL if case == "fast" else None)
+
+
 # ------------------------------------------------------------------ the five named configurations
 
 def check_config_sampled(cfg, n_random, heads=None):

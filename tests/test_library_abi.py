@@ -100,7 +100,9 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.kernel = 9
     assert _call(lib, opts=o) == 3
-    o = AttnJvpOpts(); o.reserved[1] = 1
+    o = AttnJvpOpts(); o.reserved = 1
+    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.layout = 2                        # unknown layout
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.flags = 8                         # unknown flag bit
     assert _call(lib, opts=o) == 3
