@@ -19,6 +19,71 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 
 
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+
+
+def bench_rmsnorm(args, cfg, dev):
+    """RMSNorm + JVP over every (batch, head, token) row of the workload's q and tq: reads x, tx, writes y, ty."""
+    import numpy as np
+    import torch
+    from paper_2510_08431_amd import binding
+    from paper_2510_08431_amd.workloads import make_inputs
+    t = make_inputs(cfg)
+    x, tx = t["q"].to(dev), t["tq"].to(dev)
+    w = (1.0 + 0.1 * torch.randn(cfg.d, generator=torch.Generator().manual_seed(7))).to(dev)
+    y, ty = torch.empty_like(x), torch.empty_like(tx)
+    eps = 1e-6
+    rows = x.numel() // cfg.d
+    nbytes = 4 * x.numel() * x.element_size()
+
+    def step():
+        binding.attn_jvp_rmsnorm_fwd(x, tx, w, eps, out=(y, ty))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for a, b in evs:          # one kernel per step, launched on torch's current stream: the events bracket it
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kern_ms = [a.elapsed_time(b) for a, b in evs]
+    ms_per_step = wall * 1e3 / args.steps
+    gbs = nbytes / (ms_per_step * 1e-3) / 1e9
+    kern_gbs = nbytes / (float(np.mean(kern_ms)) * 1e-3) / 1e9
+    out = {
+        "metric": "RMSNorm+JVP GB/s (x, tx read, y, ty written once)", "value": round(gbs, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"qk-norm of {cfg.name}", "rows": rows, "d": cfg.d},
+        "roofline": {"bound": "hbm", "achieved": round(kern_gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": round(kern_gbs / PEAK_HBM_GBS, 4), "traffic": None, "kernel": "rmsnorm_jvp_kernel",
+                     "kernel_ms_avg": round(float(np.mean(kern_ms)), 4), "kernel_ms_min": round(float(np.min(kern_ms)), 4)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle.rmsnorm_jvp_ref import rmsnorm_jvp_ref
+        n = min(rows, 2_000_000)
+        xs = t["q"].reshape(-1, cfg.d)[:n].double().numpy()
+        txs = t["tq"].reshape(-1, cfg.d)[:n].double().numpy()
+        ws = w.cpu().double().numpy()
+        c0 = time.perf_counter()
+        reps = 0
+        while time.perf_counter() - c0 < 10.0:
+            rmsnorm_jvp_ref(xs, txs, ws, eps)
+            reps += 1
+        cpu_s = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": round(reps * 4 * n * cfg.d * x.element_size() / cpu_s / 1e9, 3), "unit": "GB/s",
+                               "cores": torch.get_num_threads(), "kind": "oracle",
+                               "sample": f"{n} rows x {reps} repetitions, fp64 numpy, {cpu_s:.1f} s "
+                                         "(bytes counted as for the bf16 kernel)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -35,6 +100,9 @@ def main():
                          "the kernel then executes 8*Lq*Lkv*d flop per head, the metric still counts 12")
     ap.add_argument("--layout", choices=["bhld", "blhd"], default="bhld",
                     help="memory layout of the eight tensors: [B,H,L,d] (default) or [B,L,H,d]")
+    ap.add_argument("--op", choices=["attention", "rmsnorm"], default="attention",
+                    help="attention (default: the headline metric) or rmsnorm: the RMSNorm + JVP kernel on the q tensor "
+                         "of the chosen workload (its QK-normalisation), an HBM-bound second workload with its own line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (known traffic) for scaling HBM counters")
@@ -66,6 +134,9 @@ def main():
     cfg = CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.op == "rmsnorm":
+        bench_rmsnorm(args, cfg, dev)
+        return
     t = {n: x.to(dev) for n, x in make_inputs(cfg).items()}
     B, H, Lq, Lkv, d = cfg.B, cfg.H, cfg.Lq, cfg.Lkv, cfg.d
     layout = binding.LAYOUT_BHLD

@@ -128,6 +128,22 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v,
  */
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 
+/*
+ * RMS normalisation with gain and its JVP, the QK-normalisation in front of the attention (paper App. C.2, the
+ * RMSNorm layer restructured for JVP mode).  For each of `rows` rows of length d:
+ *
+ *     r = 1 / sqrt(mean(x^2) + eps)     y = cast(x r) w     ty = cast(tx r - x r^3 mean(x tx)) w
+ *
+ * cast() rounds to the dtype of x before the gain is applied, as the layer does (normalise in float32, cast back,
+ * multiply by the weight); y, ty are rounded once more on storing.  x, tx, y, ty: [rows, d] contiguous DEVICE
+ * arrays of `dtype` (ATTN_JVP_BF16 or ATTN_JVP_FP32), 16-byte aligned; w: [d] float32 DEVICE array.  d in
+ * {64, 128, 256}.  y may be x and ty may be tx (in place); no other overlap.  eps >= 0.  Enqueues one kernel on
+ * `stream` (hipStream_t, NULL = default) and returns an ATTN_JVP_* code without synchronising; on a non-zero
+ * return nothing was launched.
+ */
+int attn_jvp_rmsnorm_fwd(const void* x, const void* tx, const float* w, void* y, void* ty,
+                         long long rows, int d, float eps, int dtype, void* stream);
+
 /* Static, NUL-terminated description of an error code (never NULL). */
 const char* attn_jvp_strerror(int code);
 

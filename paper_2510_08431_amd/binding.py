@@ -56,6 +56,8 @@ def load_library():
     lib.attn_jvp_strerror.restype = ctypes.c_char_p
     lib.attn_jvp_version.argtypes = []
     lib.attn_jvp_version.restype = ci
+    lib.attn_jvp_rmsnorm_fwd.argtypes = [vp] * 5 + [ctypes.c_longlong, ci, ctypes.c_float, ci, vp]
+    lib.attn_jvp_rmsnorm_fwd.restype = ci
     lib.attn_jvp_workspace_bytes.argtypes = [ci] * 5
     lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
     _lib = lib
@@ -176,6 +178,38 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     if rc != 0:
         raise AttnJvpError(rc, attn_jvp_strerror(rc))
     return o, to, lse
+
+
+def attn_jvp_rmsnorm_fwd(x, tx, w, eps, out=None, stream=None):
+    """Enqueue y, ty = RMS normalisation with gain w and its JVP over the last dimension.
+
+    x, tx: [..., d] bf16 or fp32, contiguous, on the GPU; w: [d] float32.  out: optional (y, ty) to write into
+    (may be (x, tx) themselves).  Returns (y, ty); asynchronous."""
+    lib = load_library()
+    if x.dtype not in _DTYPE_CODE or tx.dtype != x.dtype or tuple(tx.shape) != tuple(x.shape):
+        raise ValueError("x and tx must have the same shape and dtype (bf16 or fp32)")
+    if not (x.is_cuda and tx.is_cuda and w.is_cuda):
+        raise ValueError("tensors must live on the GPU; there is no CPU path")
+    if not (x.is_contiguous() and tx.is_contiguous() and w.is_contiguous()):
+        raise ValueError("x, tx and w must be contiguous")
+    d = x.shape[-1]
+    if w.dtype != torch.float32 or tuple(w.shape) != (d,):
+        raise ValueError("w must be a float32 vector of length d")
+    rows = x.numel() // d
+    if out is None:
+        y, ty = torch.empty_like(x), torch.empty_like(tx)
+    else:
+        y, ty = out
+        if y.dtype != x.dtype or ty.dtype != x.dtype or tuple(y.shape) != tuple(x.shape) or tuple(ty.shape) != tuple(x.shape):
+            raise ValueError("out must be (y, ty) shaped and typed like x")
+    if stream is None:
+        stream = torch.cuda.current_stream(x.device)
+    with torch.cuda.device(x.device):
+        rc = lib.attn_jvp_rmsnorm_fwd(x.data_ptr(), tx.data_ptr(), w.data_ptr(), y.data_ptr(), ty.data_ptr(),
+                                      rows, d, float(eps), _DTYPE_CODE[x.dtype], stream.cuda_stream)
+    if rc != 0:
+        raise AttnJvpError(rc, attn_jvp_strerror(rc))
+    return y, ty
 
 
 def attn_jvp_fwd(q, k, v, tq, tk, tv, scale, out=None):

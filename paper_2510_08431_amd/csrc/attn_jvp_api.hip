@@ -73,6 +73,20 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v, const void* tq,
     return run(q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale, opts);
 }
 
+int attn_jvp_rmsnorm_fwd(const void* x, const void* tx, const float* w, void* y, void* ty,
+                         long long rows, int d, float eps, int dtype, void* stream) {
+    if (!x || !tx || !w || !y || !ty) return ATTN_JVP_NULL_PTR;
+    if (rows <= 0 || d <= 0 || !std::isfinite(eps) || eps < 0.f) return ATTN_JVP_BAD_SHAPE;
+    if ((long double)rows * d > 4.0e18L) return ATTN_JVP_BAD_SHAPE;
+    if (dtype != ATTN_JVP_BF16 && dtype != ATTN_JVP_FP32) return ATTN_JVP_UNSUPPORTED;
+    const void* ptrs[] = {x, tx, w, y, ty};
+    for (const void* p : ptrs)
+        if (!aligned16(p)) return ATTN_JVP_MISALIGNED;
+    attn_jvp::RmsNormProblem p{x, tx, w, y, ty, (long)rows, d, eps, dtype, static_cast<hipStream_t>(stream)};
+    if (!attn_jvp::rmsnorm_jvp_supports(p)) return ATTN_JVP_UNSUPPORTED;
+    return attn_jvp::launch_rmsnorm_jvp(p) == hipSuccess ? ATTN_JVP_OK : ATTN_JVP_LAUNCH_FAILED;
+}
+
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
     if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0 || d != 128) return 0;
     return attn_jvp::f16_workspace_bytes(B, H, Lq, Lkv, d);

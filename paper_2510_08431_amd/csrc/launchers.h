@@ -56,4 +56,18 @@ struct F16Workspace {
 size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out);
 
+// RMS normalisation with gain + JVP over `rows` rows of length d
+struct RmsNormProblem {
+    const void *x, *tx;
+    const float* w;
+    void *y, *ty;
+    long rows;
+    int d;
+    float eps;
+    int dtype;      // 0 bf16, 1 fp32 (x, tx, y, ty)
+    hipStream_t stream;
+};
+bool rmsnorm_jvp_supports(const RmsNormProblem& p);
+hipError_t launch_rmsnorm_jvp(const RmsNormProblem& p);
+
 }  // namespace attn_jvp

@@ -27,7 +27,8 @@ def declared_functions():
 
 def test_header_symbols_exported(lib):
     names = declared_functions()
-    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_strerror", "attn_jvp_version", "attn_jvp_workspace_bytes"} <= set(names)
+    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_rmsnorm_fwd", "attn_jvp_strerror", "attn_jvp_version",
+            "attn_jvp_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -115,6 +116,22 @@ def test_argument_validation_returns_codes_without_launching(lib):
     for bad_scale in (0.0, -0.125):                        # MFMA kernel needs scale > 0 (AUTO then takes the fp32 kernel)
         o = AttnJvpOpts(); o.kernel = 2
         assert _call(lib, scale=bad_scale, opts=o) == 3
+
+
+def test_rmsnorm_argument_validation_returns_codes_without_launching(lib):
+    """Fake (never dereferenced) addresses: every call here must be rejected on the host."""
+    vp = ctypes.c_void_p
+    def call(ptrs=None, rows=8, d=128, eps=1e-6, dtype=0):
+        p = [0x1000 * (i + 1) for i in range(5)] if ptrs is None else ptrs
+        return lib.attn_jvp_rmsnorm_fwd(*[vp(a) for a in p], rows, d, eps, dtype, None)
+    good = [0x1000 * (i + 1) for i in range(5)]
+    for i in range(5):
+        p = list(good); p[i] = 0
+        assert call(p) == 1
+        p = list(good); p[i] += 4
+        assert call(p) == 4
+    assert call(rows=0) == 2 and call(d=0) == 2 and call(eps=-1.0) == 2 and call(eps=float("nan")) == 2
+    assert call(d=96) == 3 and call(dtype=5) == 3
 
 
 def test_binding_rejects_cpu_tensors_and_bad_shapes():
