@@ -204,7 +204,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int c = lane & 31;          // query column of this lane in every MFMA result
     const int g = lane >> 5;          // which half of the contraction index this lane feeds
-    const int bid = blockIdx.x;
+    // Workgroups are dealt to the 8 XCDs round-robin by index.  Give XCD x the x-th contiguous eighth of the
+    // (head, query tile) list, so that neighbouring tiles, whose output rows are neighbours in memory, are written
+    // through the same L2: measured, this halves the kernel's HBM write traffic (0.81 -> 0.41 GB on the video
+    // workload, the algorithmic 0.40) at unchanged run time.  (It does not reduce the K/V fetch traffic: a head's
+    // K and V do not fit an L2, so every round of 32 co-resident workgroups streams them again either way.)
+    const int n_wg = gridDim.x;
+    const int bid = (n_wg & 7) == 0 ? (int)(blockIdx.x & 7) * (n_wg >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
     const long bh = bid / q_tiles;
     const int q0 = (bid % q_tiles) * BR + wave * 32;
 

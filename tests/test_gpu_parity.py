@@ -225,7 +225,13 @@ def f16_tile_flags(B, H, Lq):
     ws = binding._workspaces[torch.device(DEV)]
     off = (B * H * 32 + 255) // 256 * 256
     n = B * H * ((Lq + 127) // 128)
-    return ws[off:off + 4 * n].view(torch.int32).cpu().numpy().reshape(B * H, -1)
+    flags = ws[off:off + 4 * n].view(torch.int32).cpu().numpy()
+    if n % 8 == 0:      # the kernel's workgroup -> tile map: workgroup w does tile (w % 8) * (n / 8) + w // 8
+        w = np.arange(n)
+        by_tile = np.empty_like(flags)
+        by_tile[(w % 8) * (n // 8) + w // 8] = flags
+        flags = by_tile
+    return flags.reshape(B * H, -1)
 
 
 def test_f16_path_routes_tiles_by_score_spread():
