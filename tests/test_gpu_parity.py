@@ -260,6 +260,31 @@ def test_f16_path_abandons_tiles_that_overflow():
     assert (flags == 1).all()
 
 
+def test_many_heads_and_a_side_stream():
+    """More heads than a grid dimension holds (the fp16 path's pre-pass cannot run: the host must take the pairs, and
+    the vector kernel must decline), on a stream other than torch's default, with a caller-owned workspace."""
+    B, H, Lq, Lkv = 1, 66000, 16, 40
+    t = random_inputs(91, B, H, Lq, Lkv, 128, torch.bfloat16)
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    scale = 128 ** -0.5
+    ws = torch.empty(binding.attn_jvp_workspace_bytes(B, H, Lq, Lkv, 128), dtype=torch.uint8, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        o, to, lse = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                             flags=binding.FLAG_F16_ALWAYS, workspace=ws)
+    side.synchronize()
+    with pytest.raises(binding.AttnJvpError):
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                kernel=binding.KERNEL_FP32)
+    heads = [0, 1, 32767, 32768, 65535, 65536, H - 1]
+    pick = lambda x: x[:, heads]
+    ref = attn_jvp_ref(*(pick(t[n]) for n in ("q", "k", "v", "tq", "tk", "tv")), scale)
+    got = tuple(pick(x).cpu().double().numpy() for x in (o, to, lse))
+    compare(got, ref, torch.bfloat16, f"H={H} on a side stream, sampled heads")
+    assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(to).all())
+
+
 # ------------------------------------------------------------------ zero key/value tangents passed as NULL
 
 def run_gpu_no_kv_tangents(t, scale, kernel, flags=0):
