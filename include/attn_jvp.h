@@ -33,7 +33,8 @@
  * Execution: a call validates its arguments on the host, enqueues the kernel on the given
  * HIP stream and returns without synchronising.  A return value of 0 means "enqueued".
  * On any non-zero return nothing was launched and the outputs are untouched.  No exception
- * or abort crosses this boundary.  Results are deterministic (no atomics).
+ * or abort crosses this boundary.  Results are deterministic (the only atomics are order-independent maxima in the
+ * fp16 path's pre-pass).
  */
 #ifndef ATTN_JVP_H_
 #define ATTN_JVP_H_
