@@ -57,7 +57,8 @@ extern "C" {
 #define ATTN_JVP_BF16 0
 #define ATTN_JVP_FP32 1
 #define ATTN_JVP_OUT_FP32  0      /* o, to are float32 (default; the accumulators' own precision) */
-#define ATTN_JVP_OUT_INPUT 1      /* o, to have the input dtype */
+#define ATTN_JVP_OUT_INPUT 1      /* o, to have the input dtype (bf16 outputs carry the bf16 rounding of each element,
+                                     up to 2^-8 of its value: more than the kernels' own error) */
 
 /* attn_jvp_opts.layout */
 #define ATTN_JVP_LAYOUT_BHLD 0    /* [B, H, L, d] (default) */

@@ -186,9 +186,9 @@ template <int MODE, bool ZT>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
-    float* __restrict__ O, float* __restrict__ tO, float* __restrict__ LSE,
+    void* __restrict__ O, void* __restrict__ tO, float* __restrict__ LSE,
     int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
-    int H, int blhd) {
+    int H, int blhd, int out_bf16) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16;
     // Hand-over between the fp16 launch and the bf16-pair launch that follows it on the same stream: the fp16
@@ -821,8 +821,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const float mu = r_row * inv_l;
     const float fo = gO * inv_l, ft = gAB * inv_l;
     if (qrow < Lq) {
-        float* Op = O + q_base + (long)qrow * row_elems + 4 * g;
-        float* tOp = tO + q_base + (long)qrow * row_elems + 4 * g;
+        const long out_off = q_base + (long)qrow * row_elems + 4 * g;
+        float* Op = static_cast<float*>(O) + out_off;
+        float* tOp = static_cast<float*>(tO) + out_off;
+        uint16_t* Ob = static_cast<uint16_t*>(O) + out_off;       // bf16 outputs: same element offsets
+        uint16_t* tOb = static_cast<uint16_t*>(tO) + out_off;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -834,8 +837,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 t4.y = (accAB[db][4 * v4 + 1] - mu * a1) * ft;
                 t4.z = (accAB[db][4 * v4 + 2] - mu * a2) * ft;
                 t4.w = (accAB[db][4 * v4 + 3] - mu * a3) * ft;
-                *reinterpret_cast<float4*>(Op + 32 * db + 8 * v4) = o4;
-                *reinterpret_cast<float4*>(tOp + 32 * db + 8 * v4) = t4;
+                if (out_bf16) {      // uniform; four bf16 = 8 bytes per lane and tensor
+                    *reinterpret_cast<uint2*>(Ob + 32 * db + 8 * v4) = make_uint2(pack_bf16(o4.x, o4.y), pack_bf16(o4.z, o4.w));
+                    *reinterpret_cast<uint2*>(tOb + 32 * db + 8 * v4) = make_uint2(pack_bf16(t4.x, t4.y), pack_bf16(t4.z, t4.w));
+                } else {
+                    *reinterpret_cast<float4*>(Op + 32 * db + 8 * v4) = o4;
+                    *reinterpret_cast<float4*>(tOp + 32 * db + 8 * v4) = t4;
+                }
             }
         // m carries `headroom` binades that l_row lacks: take them out of both before adding (exact scalings)
         if (g == 0)
@@ -850,7 +858,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 // for the latter.
 bool mfma_bf16_supports(const Problem& p) {
     const bool zt = p.tk == nullptr && p.tv == nullptr;
-    return p.in_dtype == 0 && p.out_dtype == 0 && p.d == D && p.scale > 0.f && !(zt && (p.flags & 1));
+    return p.in_dtype == 0 && p.d == D && p.scale > 0.f && !(zt && (p.flags & 1));
 }
 
 hipError_t launch_mfma_bf16(const Problem& p) {
@@ -865,7 +873,7 @@ hipError_t launch_mfma_bf16(const Problem& p) {
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
-                           (float*)p.o, (float*)p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout);
+                           p.o, p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout, p.out_dtype);
         return hipGetLastError();
     };
     // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence

@@ -396,6 +396,30 @@ def test_blhd_layout_gives_the_same_bits(case):
     compare(blhd, ref, dtype, f"[B,L,H,d] {case}", tol=FAST_TOL if case == "fast" else None)
 
 
+# ------------------------------------------------------------------ bf16 outputs
+
+@pytest.mark.parametrize("variant", list(VARIANTS) + ["fast"])
+def test_mfma_bf16_outputs_are_the_rounded_fp32_outputs(variant):
+    """out_dtype = input dtype: the MFMA kernel rounds its fp32 results to bf16 on storing (round to nearest even);
+    lse stays fp32.  Must equal torch's rounding of the fp32-output call bit for bit, in both layouts."""
+    flags = binding.FLAG_FAST if variant == "fast" else VARIANTS[variant]
+    t = random_inputs(95, 2, 2, 200, 333, 128, torch.bfloat16)
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    scale = 128 ** -0.5
+    args = (dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale)
+    o32, to32, lse32 = binding.attn_jvp_fwd_ex(*args, kernel=binding.KERNEL_MFMA, flags=flags)
+    o16, to16, lse16 = binding.attn_jvp_fwd_ex(*args, kernel=binding.KERNEL_MFMA, flags=flags, out_dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    assert o16.dtype == torch.bfloat16 and to16.dtype == torch.bfloat16 and lse16.dtype == torch.float32
+    assert torch.equal(o16, o32.to(torch.bfloat16)) and torch.equal(to16, to32.to(torch.bfloat16))
+    assert torch.equal(lse16, lse32)
+    perm = lambda x: x.permute(0, 2, 1, 3).contiguous()
+    ob, tob, _ = binding.attn_jvp_fwd_ex(*(perm(x) for x in args[:6]), scale, kernel=binding.KERNEL_MFMA, flags=flags,
+                                         out_dtype=torch.bfloat16, layout=binding.LAYOUT_BLHD)
+    torch.cuda.synchronize()
+    assert torch.equal(perm(ob), o16) and torch.equal(perm(tob), to16)
+
+
 # ------------------------------------------------------------------ the five named configurations
 
 def check_config_sampled(cfg, n_random, heads=None):
