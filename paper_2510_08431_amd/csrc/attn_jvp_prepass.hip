@@ -11,10 +11,17 @@ namespace attn_jvp {
 namespace {
 
 constexpr int D = 128;
-constexpr int ROWS_PER_BLOCK = 256;      // 256 threads: 16 lanes per row, 16 rows per pass
+constexpr int ROWS_PER_BLOCK = 1024;     // 256 threads: 16 lanes per row, 16 rows per pass, 64 passes
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// 16-byte load of data that this kernel reads exactly once
+__device__ __forceinline__ uint4 ld16(const __hip_bfloat16* p) {
+    typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
 
 __global__ void zero_stats_kernel(float* stats, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -49,8 +56,7 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
 #pragma unroll
         for (int u = 0; u < 4; ++u) {            // four independent 16-byte loads in flight per lane
             const int row = row0 + rr + 16 * u;
-            w[u] = row < L ? *reinterpret_cast<const uint4*>(X + row_offset(bh, row, L, a.H, a.blhd) + sub * 8)
-                           : make_uint4(0, 0, 0, 0);
+            w[u] = row < L ? ld16(X + row_offset(bh, row, L, a.H, a.blhd) + sub * 8) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -70,8 +76,16 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
     }
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) best = fmaxf(best, __shfl_xor(best, o));
+    // one atomic per block, not per wave: all blocks of a (head, tensor) pair hit the same address, and atomics to
+    // one address serialise in the L2 (with one per wave they, not the loads, set the kernel's run time)
+    __shared__ float wave_best[4];
+    if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
+    __syncthreads();
     // non-negative floats order like their bit patterns; NaN/inf inputs give a huge pattern and end in the fallback
-    if ((threadIdx.x & 63) == 0) atomicMax(reinterpret_cast<unsigned int*>(stats + bh * 8 + which), __float_as_uint(best));
+    if (threadIdx.x == 0) {
+        best = fmaxf(fmaxf(wave_best[0], wave_best[1]), fmaxf(wave_best[2], wave_best[3]));
+        atomicMax(reinterpret_cast<unsigned int*>(stats + bh * 8 + which), __float_as_uint(best));
+    }
 }
 
 __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat16* __restrict__ V,
