@@ -29,6 +29,8 @@
  * the keys and values carry no tangent, which is App. C.1's equations with tK = tV = 0.
  * The result is bit-identical to passing zero tensors; the MFMA kernel then streams only K and V and runs 4 of the
  * 6 matrix products (tS = s tQ K^T, tO = tP V).
+ * tq, tk and tv may ALL be NULL: no tangents, the plain attention forward that Alg. 2 extends (2 of the 6 products).
+ * o and lse are the same bits as with tangents; `to` is not written and may be NULL.
  *
  * Execution: a call validates its arguments on the host, enqueues the kernel on the given
  * HIP stream and returns without synchronising.  A return value of 0 means "enqueued".
@@ -47,7 +49,7 @@ extern "C" {
 
 /* error codes */
 #define ATTN_JVP_OK            0
-#define ATTN_JVP_NULL_PTR      1  /* a required pointer is NULL (tk and tv: exactly one of the two is NULL) */
+#define ATTN_JVP_NULL_PTR      1  /* a required pointer is NULL (tangents may be absent only as tk+tv or tq+tk+tv) */
 #define ATTN_JVP_BAD_SHAPE     2  /* B, H, Lq, Lkv or d <= 0, a product overflows, or scale is not finite */
 #define ATTN_JVP_UNSUPPORTED   3  /* head dim / dtype / kernel choice not built */
 #define ATTN_JVP_MISALIGNED    4  /* a pointer is not 16-byte aligned */
@@ -72,7 +74,7 @@ extern "C" {
 #define ATTN_JVP_KERNEL_MFMA 2    /* bf16 matrix-core kernel: bf16 inputs, d = 128, scale > 0 */
 
 /* attn_jvp_opts.flags */
-#define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only (not with tk = tv = NULL): round the weights P~ and H~ = P~ o tS to ONE bf16 term each
+#define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only (not with absent tangents): round the weights P~ and H~ = P~ o tS to ONE bf16 term each
                                      (6 matrix products per key tile, as Alg. 2 counts them) instead of the default
                                      hi + lo bf16 pairs in all three value contractions (9 products) or the fp16 value path.  Faster; the
                                      8-bit rounding then shows in the results: max errors up to ~2e-2 of RMS(O) and

@@ -110,6 +110,8 @@ def _check_inputs(q, k, v, tq, tk, tv, layout=LAYOUT_BHLD):
         raise ValueError(f"unknown layout {layout}")
     if (tk is None) != (tv is None):
         raise ValueError("tk and tv must both be given or both be None (zero key/value tangents)")
+    if tq is None and tk is not None:
+        raise ValueError("tq=None means no tangents at all: tk and tv must be None too")
     for name, t, L in (("q", q, Lq), ("tq", tq, Lq), ("k", k, Lkv), ("v", v, Lkv), ("tk", tk, Lkv), ("tv", tv, Lkv)):
         if t is None:
             continue
@@ -131,7 +133,8 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     """Enqueue O, tO, lse = attention forward + JVP on the current (or given) stream.
 
     q, tq: [B, H, Lq, d]; k, v, tk, tv: [B, H, Lkv, d]; bf16 or fp32, contiguous, on the GPU.  tk and tv may both be
-    None: zero key/value tangents (cross-attention onto a context without tangent).
+    None: zero key/value tangents (cross-attention onto a context without tangent); tq, tk, tv all None: plain
+    attention forward, the returned `to` is None.
     out: optional (o, to, lse) to write into.  workspace: "auto" (a cached per-device torch buffer), None (no
     scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  layout=LAYOUT_BLHD: all eight
     tensors are [B, L, H, d] instead (lse stays [B, H, Lq]).  timing_events: optional pair of
@@ -142,12 +145,13 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     B, H, Lq, Lkv, d = _check_inputs(q, k, v, tq, tk, tv, layout)
     if out is None:
         o = torch.empty(q.shape, dtype=out_dtype, device=q.device)     # same layout as q
-        to = torch.empty_like(o)
+        to = torch.empty_like(o) if tq is not None else None
         lse = torch.empty(B, H, Lq, dtype=torch.float32, device=q.device)
     else:
         o, to, lse = out
         out_dtype = o.dtype
-        if tuple(o.shape) != tuple(q.shape) or tuple(to.shape) != tuple(q.shape) or tuple(lse.shape) != (B, H, Lq):
+        if (tuple(o.shape) != tuple(q.shape) or tuple(lse.shape) != (B, H, Lq)
+                or (to is not None and tuple(to.shape) != tuple(q.shape)) or (to is None and tq is not None)):
             raise ValueError("out must be (o, to, lse) with o, to shaped like q and lse [B, H, Lq]")
     if out_dtype not in (torch.float32, q.dtype):
         raise ValueError("out_dtype must be float32 or the input dtype")
@@ -172,8 +176,8 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
                 ev.record(stream)
             opts.timing_events[i] = ev.cuda_event
     with torch.cuda.device(q.device):
-        rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), _ptr(tk), _ptr(tv),
-                                 o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale),
+        rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(tq), _ptr(tk), _ptr(tv),
+                                 o.data_ptr(), _ptr(to), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale),
                                  ctypes.byref(opts))
     if rc != 0:
         raise AttnJvpError(rc, attn_jvp_strerror(rc))
@@ -225,13 +229,13 @@ def attn_jvp_fwd(q, k, v, tq, tk, tv, scale, out=None):
         return attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=out, workspace=None)
     if out is None:
         o = torch.empty(B, H, Lq, d, dtype=torch.float32, device=q.device)
-        to = torch.empty_like(o)
+        to = torch.empty_like(o) if tq is not None else None
         lse = torch.empty(B, H, Lq, dtype=torch.float32, device=q.device)
     else:
         o, to, lse = out
     with torch.cuda.device(q.device):
-        rc = lib.attn_jvp_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), tq.data_ptr(), _ptr(tk), _ptr(tv),
-                              o.data_ptr(), to.data_ptr(), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale))
+        rc = lib.attn_jvp_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(tq), _ptr(tk), _ptr(tv),
+                              o.data_ptr(), _ptr(to), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale))
     if rc != 0:
         raise AttnJvpError(rc, attn_jvp_strerror(rc))
     return o, to, lse

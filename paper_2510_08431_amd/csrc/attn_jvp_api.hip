@@ -18,8 +18,10 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     def.out_dtype = ATTN_JVP_OUT_FP32;
     if (!opts) opts = &def;
 
-    if (!q || !k || !v || !tq || !o || !to || !lse) return ATTN_JVP_NULL_PTR;
+    if (!q || !k || !v || !o || !lse) return ATTN_JVP_NULL_PTR;
     if ((tk == nullptr) != (tv == nullptr)) return ATTN_JVP_NULL_PTR;   // zero key/value tangents come as a pair
+    if (!tq && tk) return ATTN_JVP_NULL_PTR;                            // no query tangent: no tangents at all
+    if (tq && !to) return ATTN_JVP_NULL_PTR;                            // `to` may be NULL only when there is no tangent
     if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0 || d <= 0) return ATTN_JVP_BAD_SHAPE;
     if (!std::isfinite(scale)) return ATTN_JVP_BAD_SHAPE;
     // element counts must stay far below 2^62 so that byte offsets fit in 64 bits; B*H must fit a grid dimension
@@ -31,7 +33,7 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     if (opts->reserved != 0) return ATTN_JVP_UNSUPPORTED;
     if (opts->flags & ~(ATTN_JVP_FLAG_FAST | ATTN_JVP_FLAG_NO_F16 | ATTN_JVP_FLAG_F16_ALWAYS)) return ATTN_JVP_UNSUPPORTED;
     if (opts->workspace && (reinterpret_cast<uintptr_t>(opts->workspace) & 255u)) return ATTN_JVP_MISALIGNED;
-    const void* ptrs[] = {q, k, v, tq, tk, tv, o, to, lse};
+    const void* ptrs[] = {q, k, v, tq, tk, tv, o, to, lse};   // (NULL passes the alignment test)
     for (const void* p : ptrs)
         if (!aligned16(p)) return ATTN_JVP_MISALIGNED;
 

@@ -80,7 +80,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         q[c] = Ld<TIn>::load4(Qb + 4 * (part + 4 * c));
-        tq[c] = Ld<TIn>::load4(tQb + 4 * (part + 4 * c));
+        tq[c] = tQ ? Ld<TIn>::load4(tQb + 4 * (part + 4 * c)) : make_float4(0.f, 0.f, 0.f, 0.f);   // absent: zero
         acc_o[c] = make_float4(0.f, 0.f, 0.f, 0.f);
         acc_ab[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -163,7 +163,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
             t4.z = (ab.z - mu * o4.z) * inv_l; t4.w = (ab.w - mu * o4.w) * inv_l;
             o4.x *= inv_l; o4.y *= inv_l; o4.z *= inv_l; o4.w *= inv_l;
             store4<TOut>(Ob + 4 * (part + 4 * c), o4);
-            store4<TOut>(tOb + 4 * (part + 4 * c), t4);
+            if (tO) store4<TOut>(tOb + 4 * (part + 4 * c), t4);   // no tangent asked for: nothing to store
         }
         if (part == 0) LSE[bh * Lq + qrow] = m + logf(l);
     }

@@ -177,12 +177,16 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int
 //                  powers of two so that nothing over- or underflows): 6 products, 11-bit weights.
 //
 // ZT ("zero key/value tangents", cross-attention onto a context that does not depend on the differentiated
-// variable): tK = tV = 0 are not passed at all.  tS = scale tQ K^T and tO = tP V then need 4 of the 6 products, and
+// variable; template value TAN_QUERY): tK = tV = 0 are not passed at all.  tS = scale tQ K^T and tO = tP V then need 4 of the 6 products, and
 // only K and V are streamed; the stage layout stays the same, the tangent halves are simply never written or read.
 constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2;
 constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
-template <int MODE, bool ZT>
+// TAN selects which tangents exist: TAN_ALL (tQ, tK, tV), TAN_QUERY (tQ only: "ZT" below, zero key/value tangents)
+// or TAN_NONE (plain attention forward, O and lse only: 2 of the 6 products; same code path, nothing else changes).
+constexpr int TAN_NONE = 0, TAN_QUERY = 1, TAN_ALL = 2;
+
+template <int MODE, int TAN>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
@@ -191,6 +195,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     int H, int blhd, int out_bf16) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16;
+    constexpr bool ZT = TAN != TAN_ALL;          // no key/value tangents
+    constexpr bool PRIMAL = TAN == TAN_NONE;     // no tangents at all
     // Hand-over between the fp16 launch and the bf16-pair launch that follows it on the same stream: the fp16
     // kernel writes wg_flags[workgroup] = 1 for every tile it declines or abandons (and 0 otherwise) and stores
     // nothing for those; the pair kernel, given the flags, works on exactly those tiles.
@@ -276,11 +282,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         const bf16x8* qp = reinterpret_cast<const bf16x8*>(Q + q_base + (long)qrow_ld * row_elems + 8 * g);
         const bf16x8* tqp = reinterpret_cast<const bf16x8*>(tQ + q_base + (long)qrow_ld * row_elems + 8 * g);
 #pragma unroll
-        for (int t = 0; t < 8; ++t) { qf[t] = qp[2 * t]; tqf[t] = tqp[2 * t]; }
+        for (int t = 0; t < 8; ++t) {
+            qf[t] = qp[2 * t];
+            if constexpr (!PRIMAL) tqf[t] = tqp[2 * t];
+        }
 #pragma unroll
         for (int t = 0; t < 8; ++t) {   // keep them in accumulation registers: only MFMAs read them
             asm volatile("" : "+a"(qf[t]));
-            asm volatile("" : "+a"(tqf[t]));
+            if constexpr (!PRIMAL) asm volatile("" : "+a"(tqf[t]));
         }
     }
 
@@ -331,17 +340,19 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             sp0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
             sp1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
         } else if constexpr (part == 1) {
-            sh0 = sp0 * fmaf(tsv[e], scale_h, -ctr_h);
-            sh1 = sp1 * fmaf(tsv[e + 1], scale_h, -ctr_h);
+            if constexpr (!PRIMAL) {
+                sh0 = sp0 * fmaf(tsv[e], scale_h, -ctr_h);
+                sh1 = sp1 * fmaf(tsv[e + 1], scale_h, -ctr_h);
+            }
         } else if constexpr (part == 2) {
             l_part += sp0 + sp1;
-            r_part += sh0 + sh1;
+            if constexpr (!PRIMAL) r_part += sh0 + sh1;
         } else if constexpr (part == 3) {
             const uint32_t ph = F16 ? pack_f16(sp0, sp1) : pack_bf16(sp0, sp1);
             wp[j] = ph;
             if constexpr (SPLIT)   // lo = x - hi (exact in fp32), rounded to bf16
                 wpl[j] = pack_bf16(sp0 - __uint_as_float(ph << 16), sp1 - __uint_as_float(ph & 0xffff0000u));
-        } else if constexpr (part == 4) {
+        } else if constexpr (part == 4 && !PRIMAL) {
             const uint32_t hh = F16 ? pack_f16(sh0, sh1) : pack_bf16(sh0, sh1);
             wh[j] = hh;
             if constexpr (SPLIT)
@@ -365,8 +376,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{});
             if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}); softmax_part(J, std::integral_constant<int, 3>{}); }
             if constexpr (slot == 2) { softmax_part(J, std::integral_constant<int, 2>{}); softmax_part(J, std::integral_constant<int, 4>{}); }
+        } else if constexpr (n_slots == 1) {
+            if constexpr (slot == 0) static_for<5>([&](auto PART) { softmax_part(J, PART); });
         } else {
-            static_assert(n_slots == 2, "a pair gets 2, 3, 4 or at least 5 MFMA slots");
+            static_assert(n_slots == 2, "a pair gets 1, 2, 3, 4 or at least 5 MFMA slots");
             if constexpr (slot == 0) { softmax_part(J, std::integral_constant<int, 0>{}); softmax_part(J, std::integral_constant<int, 1>{}); }
             if constexpr (slot == 1) {
                 softmax_part(J, std::integral_constant<int, 2>{}); softmax_part(J, std::integral_constant<int, 3>{});
@@ -391,7 +404,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         for (int t = 0; t < 8; ++t) {
             const bf16x8 kf = lds_read_b128(kaddr0[t] + stage_off);
             s = MFMA(kf, qf[t], s);
-            ts = MFMA(kf, tqf[t], ts);
+            if constexpr (!PRIMAL) ts = MFMA(kf, tqf[t], ts);
             if constexpr (!ZT) ts = MFMA(lds_read_b128(kaddr0[t] + stage_off + TENSOR_BYTES), qf[t], ts);
         }
 #pragma unroll
@@ -408,7 +421,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
             const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
-            const bf16x8 hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
+            bf16x8 hb8 = pb;
+            if constexpr (!PRIMAL) hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
 #pragma unroll
             for (int db = 0; db < 4; ++db) {
                 const uint32_t a = vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
@@ -418,13 +432,15 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                     tvf = join_tr(lds_read_tr_b64(a + TENSOR_BYTES), lds_read_tr_b64(a + TENSOR_BYTES + 8 * ROW_BYTES));
                 accO[db] = VMFMA(vf, pb, accO[db]);
                 if constexpr (!ZT) accAB[db] = VMFMA(tvf, pb, accAB[db]);
-                accAB[db] = VMFMA(vf, hb8, accAB[db]);
+                if constexpr (!PRIMAL) accAB[db] = VMFMA(vf, hb8, accAB[db]);
                 if constexpr (SPLIT) {
                     const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
-                    const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
                     accO[db] = VMFMA(vf, pl8, accO[db]);
                     if constexpr (!ZT) accAB[db] = VMFMA(tvf, pl8, accAB[db]);
-                    accAB[db] = VMFMA(vf, hl8, accAB[db]);
+                    if constexpr (!PRIMAL) {
+                        const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
+                        accAB[db] = VMFMA(vf, hl8, accAB[db]);
+                    }
                 }
             }
         }
@@ -604,7 +620,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     auto iteration = [&](auto Uc, auto FULLc, int b) __attribute__((always_inline)) {
         constexpr int U = decltype(Uc)::value;
         constexpr bool FULL = decltype(FULLc)::value;
-        constexpr int PRODUCTS = ZT ? 2 : 3;                      // matrix products per score step / per weight term
+        constexpr int PRODUCTS = PRIMAL ? 1 : ZT ? 2 : 3;         // matrix products per score step / per weight term
         constexpr int GROUP_MFMAS = SPLIT ? 2 * PRODUCTS : PRODUCTS;
         using NS_P1 = std::integral_constant<int, 2 * PRODUCTS>;  // phase 1: two score steps per pair
         using NS_P2 = std::integral_constant<int, GROUP_MFMAS>;   // phase 2: one value group per pair
@@ -622,9 +638,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             s = MFMA(kfr[t % KRING], qf[t], s);
             softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{});
             FENCE();
-            ts = MFMA(kfr[t % KRING], tqf[t], ts);
-            softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{});
-            FENCE();
+            if constexpr (!PRIMAL) {
+                ts = MFMA(kfr[t % KRING], tqf[t], ts);
+                softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{});
+                FENCE();
+            }
             if constexpr (!ZT) {
                 ts = MFMA(tkfr[t % KRING], qf[t], ts);
                 softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{});
@@ -651,7 +669,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 if ((b + 2) * BC > Lkv) mask_scores(b + 1);
             }
             const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
-            const bf16x8 hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
+            bf16x8 hb8 = pb;
+            if constexpr (!PRIMAL) hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
             // vector work behind MFMA number `slot` of this group
             auto behind = [&](auto SLOT) __attribute__((always_inline)) {
                 constexpr int slot = decltype(SLOT)::value;
@@ -659,10 +678,20 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                     // scores of block b+1 out of the MFMA result registers: elements 4 gi .. 4 gi + 3
                     // (the empty asm pins each copy to this point; otherwise the compiler sinks them all to their uses)
                     constexpr int first = GROUP_MFMAS >= 3 ? 1 : 0;   // the two slots that carry the fetch
-                    if constexpr (slot == first || slot == first + 1) {
-                        constexpr int e0 = 4 * gi + 2 * (slot - first);
-                        sv[e0] = s[e0]; sv[e0 + 1] = s[e0 + 1]; tsv[e0] = ts[e0]; tsv[e0 + 1] = ts[e0 + 1];
-                        asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]), "+v"(tsv[e0]), "+v"(tsv[e0 + 1]));
+                    auto fetch = [&](auto E0) __attribute__((always_inline)) {
+                        constexpr int e0 = decltype(E0)::value;
+                        sv[e0] = s[e0]; sv[e0 + 1] = s[e0 + 1];
+                        if constexpr (PRIMAL) {
+                            asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]));
+                        } else {
+                            tsv[e0] = ts[e0]; tsv[e0 + 1] = ts[e0 + 1];
+                            asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]), "+v"(tsv[e0]), "+v"(tsv[e0 + 1]));
+                        }
+                    };
+                    if constexpr (GROUP_MFMAS == 1) {        // a single slot carries both halves
+                        if constexpr (slot == 0) { fetch(std::integral_constant<int, 4 * gi>{}); fetch(std::integral_constant<int, 4 * gi + 2>{}); }
+                    } else if constexpr (slot == first || slot == first + 1) {
+                        fetch(std::integral_constant<int, 4 * gi + 2 * (slot - first)>{});
                     }
                 } else {
                     softmax_slot(std::integral_constant<int, gi - 4>{}, SLOT, NS_P2{});
@@ -676,22 +705,26 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 behind(std::integral_constant<int, 1>{});
                 FENCE();
             }
-            accAB[db] = VMFMA(vfr[gi % VRING], hb8, accAB[db]);
-            behind(std::integral_constant<int, PRODUCTS - 1>{});
+            if constexpr (!PRIMAL) {
+                accAB[db] = VMFMA(vfr[gi % VRING], hb8, accAB[db]);
+                behind(std::integral_constant<int, PRODUCTS - 1>{});
+            }
             if constexpr (SPLIT) {
                 const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
-                const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
                 FENCE();
                 accO[db] = VMFMA(vfr[gi % VRING], pl8, accO[db]);
                 behind(std::integral_constant<int, PRODUCTS>{});
-                FENCE();
                 if constexpr (!ZT) {
+                    FENCE();
                     accAB[db] = VMFMA(tvfr[gi % VRING], pl8, accAB[db]);
                     behind(std::integral_constant<int, PRODUCTS + 1>{});
-                    FENCE();
                 }
-                accAB[db] = VMFMA(vfr[gi % VRING], hl8, accAB[db]);
-                behind(std::integral_constant<int, 2 * PRODUCTS - 1>{});
+                if constexpr (!PRIMAL) {
+                    const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
+                    FENCE();
+                    accAB[db] = VMFMA(vfr[gi % VRING], hl8, accAB[db]);
+                    behind(std::integral_constant<int, 2 * PRODUCTS - 1>{});
+                }
             }
             FENCE();
             issue_copy_piece(FULLc, Gc, b);
@@ -747,7 +780,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #pragma unroll
             for (int db = 0; db < 4; ++db)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) tot += fabsf(accO[db][e]) + fabsf(accAB[db][e]);
+                for (int e = 0; e < 16; ++e) tot += fabsf(accO[db][e]) + (PRIMAL ? 0.f : fabsf(accAB[db][e]));
             bad = bad || !(tot < 3.0e38f);
         }
         __syncthreads();                       // everyone is done with the rings
@@ -803,7 +836,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
-                        accAB[db][e] = fmaf(accAB[db][e], alpha, -da * accO[db][e]);
+                        if constexpr (!PRIMAL) accAB[db][e] = fmaf(accAB[db][e], alpha, -da * accO[db][e]);
                         accO[db][e] *= alpha;
                     }
                 static_for<8>([&](auto P) { softmax_pair(P); });
@@ -839,10 +872,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 t4.w = (accAB[db][4 * v4 + 3] - mu * a3) * ft;
                 if (out_bf16) {      // uniform; four bf16 = 8 bytes per lane and tensor
                     *reinterpret_cast<uint2*>(Ob + 32 * db + 8 * v4) = make_uint2(pack_bf16(o4.x, o4.y), pack_bf16(o4.z, o4.w));
-                    *reinterpret_cast<uint2*>(tOb + 32 * db + 8 * v4) = make_uint2(pack_bf16(t4.x, t4.y), pack_bf16(t4.z, t4.w));
+                    if constexpr (!PRIMAL)
+                        *reinterpret_cast<uint2*>(tOb + 32 * db + 8 * v4) = make_uint2(pack_bf16(t4.x, t4.y), pack_bf16(t4.z, t4.w));
                 } else {
                     *reinterpret_cast<float4*>(Op + 32 * db + 8 * v4) = o4;
-                    *reinterpret_cast<float4*>(tOp + 32 * db + 8 * v4) = t4;
+                    if constexpr (!PRIMAL) *reinterpret_cast<float4*>(tOp + 32 * db + 8 * v4) = t4;
                 }
             }
         // m carries `headroom` binades that l_row lacks: take them out of both before adding (exact scalings)
@@ -857,7 +891,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 // tk and tv are either both given or both absent (zero key/value tangents); single bf16 weights (FAST) are not built
 // for the latter.
 bool mfma_bf16_supports(const Problem& p) {
-    const bool zt = p.tk == nullptr && p.tv == nullptr;
+    const bool zt = p.tk == nullptr && p.tv == nullptr;     // (the API admits absent tangents only as tk+tv or tq+tk+tv)
     return p.in_dtype == 0 && p.d == D && p.scale > 0.f && !(zt && (p.flags & 1));
 }
 
@@ -889,23 +923,30 @@ hipError_t launch_mfma_bf16(const Problem& p) {
     }
     MainKernelTimer timer(p);
     hipError_t e;
-    if (p.tk == nullptr) {      // zero key/value tangents (the API admits them only as a pair)
+    if (p.tq == nullptr) {             // no tangents at all: plain attention forward
         if (f16) {
-            e = launch(attn_jvp_mfma_kernel<MODE_F16, true>, ws.v16, nullptr, ws.stats, ws.wg_flags);
-            if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, true>, p.v, nullptr, nullptr, ws.wg_flags);
+            e = launch(attn_jvp_mfma_kernel<MODE_F16, TAN_NONE>, ws.v16, nullptr, ws.stats, ws.wg_flags);
+            if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_NONE>, p.v, nullptr, nullptr, ws.wg_flags);
         } else {
-            e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, true>, p.v, nullptr, nullptr, nullptr);
+            e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_NONE>, p.v, nullptr, nullptr, nullptr);
+        }
+    } else if (p.tk == nullptr) {      // zero key/value tangents
+        if (f16) {
+            e = launch(attn_jvp_mfma_kernel<MODE_F16, TAN_QUERY>, ws.v16, nullptr, ws.stats, ws.wg_flags);
+            if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_QUERY>, p.v, nullptr, nullptr, ws.wg_flags);
+        } else {
+            e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_QUERY>, p.v, nullptr, nullptr, nullptr);
         }
     } else if (p.flags & 1) {
-        e = launch(attn_jvp_mfma_kernel<MODE_BF16, false>, p.v, p.tv, nullptr, nullptr);
+        e = launch(attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL>, p.v, p.tv, nullptr, nullptr);
     } else if (f16) {
         // every tile is finished by exactly one of the two launches: the fp16 kernel flags the tiles it declines
         // (scores too spread out for fp16 weights) or abandons (overflow found at the end of its sweep), the
         // bf16-pair kernel does those and returns at once from the others
-        e = launch(attn_jvp_mfma_kernel<MODE_F16, false>, ws.v16, ws.tv16, ws.stats, ws.wg_flags);
-        if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, false>, p.v, p.tv, nullptr, ws.wg_flags);
+        e = launch(attn_jvp_mfma_kernel<MODE_F16, TAN_ALL>, ws.v16, ws.tv16, ws.stats, ws.wg_flags);
+        if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_ALL>, p.v, p.tv, nullptr, ws.wg_flags);
     } else {
-        e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, false>, p.v, p.tv, nullptr, nullptr);
+        e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_ALL>, p.v, p.tv, nullptr, nullptr);
     }
     return timer.finish(e);
 }

@@ -345,6 +345,57 @@ def test_config4_null_kv_tangents_default_path():
         compare(tuple(x[:, h:h + 1] for x in got), ref, cfg.torch_dtype, f"cfg4 tk=tv=NULL h{h}", rows=rows)
 
 
+# ------------------------------------------------------------------ no tangents at all (plain attention forward)
+
+@pytest.mark.parametrize("case", ["f16", "bf16-pairs", "vector-fp32", "default-long", "blhd-bf16-out"])
+def test_no_tangents_gives_the_same_o_and_lse(case):
+    """tq = tk = tv = NULL: the kernels run only S = s Q K^T and O = P V.  O and lse must be the very bits of the
+    call with tangents (the tangent products never touch them), `to` is not written; plus oracle parity."""
+    B, H, Lq, Lkv, d, dtype, kernel, flags = 2, 2, 200, 333, 128, torch.bfloat16, binding.KERNEL_MFMA, 0
+    kw = {}
+    if case == "f16":
+        flags = binding.FLAG_F16_ALWAYS
+    elif case == "bf16-pairs":
+        flags = binding.FLAG_NO_F16
+    elif case == "vector-fp32":
+        d, dtype, kernel = 64, torch.float32, binding.KERNEL_FP32
+    elif case == "default-long":
+        B, H, Lq, Lkv, kernel = 1, 2, 260, 4100, binding.KERNEL_AUTO
+    elif case == "blhd-bf16-out":
+        kw = dict(layout=binding.LAYOUT_BLHD, out_dtype=torch.bfloat16)
+    t = random_inputs(800 + len(case), B, H, Lq, Lkv, d, dtype)
+    prep = (lambda x: x.permute(0, 2, 1, 3).contiguous()) if "layout" in kw else (lambda x: x)
+    dev = {n: prep(x.to(DEV)) for n, x in t.items()}
+    scale = d ** -0.5
+    o1, to1, lse1 = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                            kernel=kernel, flags=flags, **kw)
+    o0, to0, lse0 = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], None, None, None, scale,
+                                            kernel=kernel, flags=flags, **kw)
+    torch.cuda.synchronize()
+    assert to0 is None
+    assert torch.equal(o0, o1) and torch.equal(lse0, lse1)
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    got_o = prep(o0).float().cpu().double().numpy() if "layout" in kw else o0.float().cpu().double().numpy()
+    e_o, e_lse = rel_err(got_o, ref[0]), float(np.abs(lse0.cpu().double().numpy() - ref[2]).max())
+    print(f"[no tangents, {case}] err O={e_o:.3e} lse={e_lse:.3e}", flush=True)
+    tol_o = 2e-2 if case == "blhd-bf16-out" else TOL[dtype][0]      # bf16 outputs carry their own rounding
+    assert e_o <= tol_o and e_lse <= TOL[dtype][2]
+
+
+def test_no_tangents_argument_rules():
+    t = random_inputs(79, 1, 1, 64, 64, 128, torch.bfloat16)
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    with pytest.raises(ValueError):            # a key tangent without a query tangent makes no sense to the binding
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], None, dev["tk"], dev["tv"], 0.1)
+    with pytest.raises(binding.AttnJvpError):  # single-bf16 weights are not built without tangents
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], None, None, None, 0.1,
+                                kernel=binding.KERNEL_MFMA, flags=binding.FLAG_FAST)
+    o, to, lse = binding.attn_jvp_fwd(dev["q"], dev["k"], dev["v"], None, None, None, 0.1)    # the plain C entry point
+    o2, _, lse2 = binding.attn_jvp_fwd(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], 0.1)
+    torch.cuda.synchronize()
+    assert to is None and torch.equal(o, o2) and torch.equal(lse, lse2)
+
+
 # ------------------------------------------------------------------ [B, L, H, d] layout
 
 def run_gpu_blhd(t, scale, kernel, flags=0, null_kv=False):

@@ -83,6 +83,10 @@ def test_argument_validation_returns_codes_without_launching(lib):
     for i in range(9):
         p = list(good); p[i] = 0
         assert _call(lib, p) == 1                         # NULL_PTR
+    p = list(good); p[3] = 0; p[4] = 0                    # tq and tk absent but tv given
+    assert _call(lib, p) == 1
+    p = list(good); p[3] = p[4] = p[5] = p[7] = 0         # no tangents and no `to`: legal, the next check decides
+    assert _call(lib, p, dims=(1, 1, 8, 8, 48)) == 3
     p = list(good); p[4] = 0; p[5] = 0                    # tk = tv = NULL is legal: the next check decides
     assert _call(lib, p, dims=(1, 1, 8, 8, 48)) == 3      # ... here the unsupported head dim
     for i in range(5):
