@@ -198,7 +198,8 @@ def main():
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
                      "kernel": "attn_jvp_mfma_kernel" if cfg.dtype == "bf16" and d == 128 else "attn_jvp_fp32_kernel",
-                     "kernel_ms_avg": round(kern_avg_ms, 4), "kernel_ms_min": round(float(np.min(kern_ms)), 4)},
+                     "kernel_ms_avg": round(kern_avg_ms, 4), "kernel_ms_min": round(float(np.min(kern_ms)), 4),
+                     "kernel_ms_median": round(float(np.median(kern_ms)), 4)},
     }
 
     if not args.no_cpu_baseline:

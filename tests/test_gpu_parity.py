@@ -36,7 +36,10 @@ def compare(got, ref, dtype, label, rows=None, tol=None):
     o_ref, to_ref, lse_ref = ref
     tol_o, tol_to, tol_lse = tol or TOL[dtype]
     e_o, e_to, e_lse = rel_err(o, o_ref), rel_err(to, to_ref), float(np.abs(lse - lse_ref).max())
-    print(f"[{label}] err O={e_o:.3e} tO={e_to:.3e} lse={e_lse:.3e}", flush=True)
+    # secondary report: squared relative L2 error, the form the paper uses for its BF16-vs-FP32 comparison (App. F.2)
+    l2 = lambda a, b: float(((a - b) ** 2).sum() / max((b ** 2).sum(), 1e-300))
+    print(f"[{label}] err O={e_o:.3e} tO={e_to:.3e} lse={e_lse:.3e}   rel-L2^2 O={l2(o, o_ref):.2e} tO={l2(to, to_ref):.2e}",
+          flush=True)
     assert np.isfinite(o).all() and np.isfinite(to).all() and np.isfinite(lse).all(), label
     assert e_o <= tol_o, f"{label}: O error {e_o}"
     assert e_to <= tol_to, f"{label}: tO error {e_to}"
