@@ -263,6 +263,65 @@ def test_f16_path_abandons_tiles_that_overflow():
     assert (flags == 1).all()
 
 
+def test_mfma_every_key_length_up_to_eleven_blocks():
+    """Every Lkv from 1 to 352: each tail length (1..8 blocks after the unrolled loop), each ragged remainder, the
+    first lengths that enter the unrolled loop (256..), for every variant and for absent key/value tangents."""
+    g = torch.Generator().manual_seed(123)
+    B, H, Lq, d, Lmax = 1, 2, 70, 128, 352
+    mk = lambda L, sd: (sd * torch.randn(B, H, L, d, generator=g)).to(torch.bfloat16)
+    full = {"q": mk(Lq, 1.0), "k": mk(Lmax, 1.0), "v": mk(Lmax, 1.0), "tq": mk(Lq, 0.5), "tk": mk(Lmax, 0.5), "tv": mk(Lmax, 0.5)}
+    dev_full = {n: x.to(DEV) for n, x in full.items()}
+    scale = d ** -0.5
+    worst = {}
+    for Lkv in range(1, Lmax + 1):
+        cut = lambda x, n: x[:, :, :Lkv].contiguous() if n in ("k", "v", "tk", "tv") else x
+        t = {n: cut(x, n) for n, x in full.items()}
+        dev = {n: cut(x, n) for n, x in dev_full.items()}
+        ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+        zero = torch.zeros_like(t["k"])
+        ref_zt = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], zero, zero, scale)
+        for name, flags, tol in (("f16", binding.FLAG_F16_ALWAYS, TOL[torch.bfloat16]),
+                                 ("bf16-pairs", binding.FLAG_NO_F16, TOL[torch.bfloat16]), ("fast", binding.FLAG_FAST, FAST_TOL)):
+            for zt in (False, True):
+                if zt and name == "fast":
+                    continue
+                tk, tv = (None, None) if zt else (dev["tk"], dev["tv"])
+                o, to, lse = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], tk, tv, scale,
+                                                     kernel=binding.KERNEL_MFMA, flags=flags)
+                r = ref_zt if zt else ref
+                if zt and Lkv == 1:      # one key, no key/value tangents: tO is identically zero, no scale to divide by
+                    assert float(to.abs().max()) <= 1e-4
+                    continue
+                e = (rel_err(o.cpu().double().numpy(), r[0]), rel_err(to.cpu().double().numpy(), r[1]),
+                     float(np.abs(lse.cpu().double().numpy() - r[2]).max()))
+                key = (name, zt)
+                worst[key] = tuple(max(a, b) for a, b in zip(worst.get(key, (0, 0, 0)), e))
+                assert e[0] <= tol[0] and e[1] <= tol[1] and e[2] <= tol[2], f"Lkv={Lkv} {name} zt={zt}: errors {e}"
+    for (name, zt), e in worst.items():
+        print(f"[Lkv 1..{Lmax} {name}{' tk=tv=NULL' if zt else ''}] worst err O={e[0]:.3e} tO={e[1]:.3e} lse={e[2]:.3e}", flush=True)
+
+
+@pytest.mark.parametrize("variant", list(VARIANTS))
+def test_mfma_query_lengths_around_tile_edges(variant):
+    """Lq just below, at and above multiples of the 32-row wave tile and the 128-row workgroup tile; rows past Lq are
+    computed from a re-read row and must never be stored (the output buffer is one row longer and checked)."""
+    for Lq in (1, 31, 32, 33, 127, 128, 129, 255, 256, 257):
+        t = random_inputs(400 + Lq, 1, 2, Lq, 100, 128, torch.bfloat16)
+        dev = {n: x.to(DEV) for n, x in t.items()}
+        # outputs with a guard row behind every head: [B, H, Lq + 1, d] viewed per head would change the layout, so
+        # the guard goes behind the whole tensor instead (the last head's ragged tile is the one that could overrun)
+        o = torch.full((1, 2, Lq, 128), float("nan"), device=DEV); to = torch.full_like(o, float("nan"))
+        lse = torch.full((1, 2, Lq), float("nan"), device=DEV)
+        guard_o = torch.full((4096,), 7.0, device=DEV)      # allocated right after; a stray store would likely land here
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], 128 ** -0.5,
+                                out=(o, to, lse), kernel=binding.KERNEL_MFMA, flags=VARIANTS[variant])
+        torch.cuda.synchronize()
+        assert bool((guard_o == 7.0).all())
+        ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], 128 ** -0.5)
+        compare((o.cpu().double().numpy(), to.cpu().double().numpy(), lse.cpu().double().numpy()), ref, torch.bfloat16,
+                f"mfma {variant} Lq={Lq}")
+
+
 def test_many_heads_and_a_side_stream():
     """More heads than a grid dimension holds (the fp16 path's pre-pass cannot run: the host must take the pairs, and
     the vector kernel must decline), on a stream other than torch's default, with a caller-owned workspace."""
