@@ -31,7 +31,8 @@
 // Numerics: bf16 operands, fp32 accumulation; softmax in base 2 with scale*log2(e) folded into one FMA.
 // The fast sweep fixes the exponent reference m per row after the first block (all of Alg. 2's rescale
 // factors become 1, so the accumulators are only ever written by MFMAs), checks at the end that this was
-// safe, and otherwise redoes the tile with Alg. 2's running maximum.  H~ = P~ o tS is formed as
+// safe, and otherwise redoes the tile with Alg. 2's running maximum (bf16 weights) or leaves it to the bf16-pair
+// launch (fp16 weights).  H~ = P~ o tS is formed as
 // P~ o (tS - ctr) with a per-row constant ctr near rowsum(P o tS): tP does not change when a constant is
 // added to a row of tS, and a small |tS - ctr| on the keys that carry the weight keeps the rounding of H~
 // from surviving the B - r O cancellation.
