@@ -318,3 +318,24 @@ def test_streaming_equals_explicit_config1_shape():
         got = alg2_head(q, k, v, tq, tk, tv, 0.125, Br, Bc)
         for x, y in zip(got, ref):
             np.testing.assert_allclose(x, y, rtol=0, atol=1e-12)
+
+
+def test_frozen_tiny_example_still_matches():
+    """tests/golden/attn_jvp_tiny.json (written by tests/golden/make_attn_jvp_tiny.py from the oracle alone) freezes
+    the oracle's answers on a 3 x 5 x 4 problem: both oracles must still reproduce it, the streaming walk too."""
+    import json
+    import os
+    from oracle.rmsnorm_jvp_ref import rmsnorm_jvp_ref
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "attn_jvp_tiny.json")) as f:
+        gold = json.load(f)
+    a = {n: np.array(x) for n, x in gold["inputs"].items()}
+    o, to, lse = attn_jvp_ref_head(a["q"], a["k"], a["v"], a["tq"], a["tk"], a["tv"], gold["scale"])
+    for got, name in ((o, "o"), (to, "to"), (lse, "lse")):
+        np.testing.assert_allclose(got, np.array(gold["attention"][name]), rtol=1e-13, atol=1e-15)
+    o2, to2, lse2 = alg2_head(a["q"], a["k"], a["v"], a["tq"], a["tk"], a["tv"], gold["scale"], 2, 2)
+    np.testing.assert_allclose(o2, np.array(gold["attention"]["o"]), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(to2, np.array(gold["attention"]["to"]), rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lse2, np.array(gold["attention"]["lse"]), rtol=1e-12, atol=1e-14)
+    y, ty = rmsnorm_jvp_ref(a["q"], a["tq"], a["w"], gold["eps"])
+    np.testing.assert_allclose(y, np.array(gold["rmsnorm_of_q"]["y"]), rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(ty, np.array(gold["rmsnorm_of_q"]["ty"]), rtol=1e-13, atol=1e-15)
