@@ -79,15 +79,17 @@ def attn_jvp_workspace_bytes(B, H, Lq, Lkv, d):
 _workspaces = {}
 
 
-def _workspace(device, nbytes):
-    """A per-device scratch tensor from torch's allocator, grown on demand and reused across calls.
+def _workspace(device, stream, nbytes):
+    """A scratch tensor from torch's allocator per (device, stream), grown on demand and reused across calls.
 
-    Calls on one device share it: like any torch tensor it is only safe to reuse in stream order, so callers
-    that overlap attention calls on several streams must pass their own `workspace`."""
-    ws = _workspaces.get(device)
+    Calls enqueued on one stream run in order, so they can share scratch; calls on different streams may overlap
+    and get separate buffers.  Callers that want to own the memory pass their own `workspace`."""
+    key = (device, stream.cuda_stream)
+    ws = _workspaces.get(key)
     if ws is None or ws.numel() < nbytes:
-        ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
-        _workspaces[device] = ws
+        with torch.cuda.stream(stream):      # so that torch's caching allocator ties the block to this stream
+            ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        _workspaces[key] = ws
     return ws
 
 
@@ -166,7 +168,7 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     opts.layout = int(layout)
     if isinstance(workspace, str) and workspace == "auto":
         need = lib.attn_jvp_workspace_bytes(B, H, Lq, Lkv, d) if q.dtype == torch.bfloat16 else 0
-        workspace = _workspace(q.device, need) if need else None
+        workspace = _workspace(q.device, stream, need) if need else None
     if workspace is not None:
         opts.workspace = workspace.data_ptr()
         opts.workspace_bytes = workspace.numel() * workspace.element_size()

@@ -225,7 +225,7 @@ def test_mfma_peaked_softmax_small():
 def f16_tile_flags(B, H, Lq):
     """Hand-over flags the last fp16-path call left in the binding's cached workspace (one int per 128-row query
     tile, after the per-head statistics): 1 = tile done by the bf16-pair launch, 0 = done by the fp16 launch."""
-    ws = binding._workspaces[torch.device(DEV)]
+    ws = binding._workspaces[(torch.device(DEV), torch.cuda.current_stream(DEV).cuda_stream)]
     off = (B * H * 32 + 255) // 256 * 256
     n = B * H * ((Lq + 127) // 128)
     flags = ws[off:off + 4 * n].view(torch.int32).cpu().numpy()
@@ -261,6 +261,33 @@ def test_f16_path_abandons_tiles_that_overflow():
     flags = f16_tile_flags(B, H, Lq)
     print("[tile flags]", flags.tolist(), flush=True)
     assert (flags == 1).all()
+
+
+def test_two_streams_get_separate_automatic_workspaces():
+    """Calls that may overlap (two streams) must not share the binding's automatic scratch: each result must be what
+    the same call gives alone."""
+    ta = random_inputs(301, 1, 2, 512, 4096, 128, torch.bfloat16)
+    tb = random_inputs(302, 1, 2, 512, 4096, 128, torch.bfloat16, tangent_std=1.0)
+    scale = 128 ** -0.5
+    alone = [run_gpu(t, scale, binding.KERNEL_MFMA) for t in (ta, tb)]
+    da = {n: x.to(DEV) for n, x in ta.items()}
+    db = {n: x.to(DEV) for n, x in tb.items()}
+    torch.cuda.synchronize()
+    sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    for _ in range(3):
+        with torch.cuda.stream(sa):
+            ra = binding.attn_jvp_fwd_ex(da["q"], da["k"], da["v"], da["tq"], da["tk"], da["tv"], scale, kernel=binding.KERNEL_MFMA)
+        with torch.cuda.stream(sb):
+            rb = binding.attn_jvp_fwd_ex(db["q"], db["k"], db["v"], db["tq"], db["tk"], db["tv"], scale, kernel=binding.KERNEL_MFMA)
+        outs.append((ra, rb))
+    torch.cuda.synchronize()
+    keys = [k for k in binding._workspaces if k[1] in (sa.cuda_stream, sb.cuda_stream)]
+    assert len(keys) == 2 and binding._workspaces[keys[0]].data_ptr() != binding._workspaces[keys[1]].data_ptr()
+    for ra, rb in outs:
+        for got, want in ((ra, alone[0]), (rb, alone[1])):
+            for g, w in zip(got, want):
+                np.testing.assert_array_equal(g.cpu().double().numpy(), w)
 
 
 def test_mfma_every_key_length_up_to_eleven_blocks():
