@@ -4,9 +4,9 @@
 // the fp32 tolerance, and it accepts bf16 inputs too (upcast exactly).  It is the path for fp32
 // inputs and head dims the matrix-core kernel does not cover; it is not tuned for speed.
 //
-// Work split: a workgroup of 256 lanes owns BR = 64 query rows; each row is shared by 4
+// Work split: a workgroup of 256 lanes owns BR = 64 query rows (16 for d = 256); each row is shared by 4 (16)
 // neighbouring lanes, lane part p holding the float4 chunks p, p+4, p+8, ... of q, tq and of the
-// three accumulators.  Key/value tiles of BC = 32 rows (K, tK, V, tV) are staged in LDS as fp32.
+// accumulators.  Key/value tiles of BC = 32 rows (K, tK, V, tV) are staged in LDS as fp32.
 // Per tile: partial dot products reduced over the 4 lanes -> S, tS; row max; P~ = exp(S - m);
 // l, r, O, A+B updated with the rescale factor exp(m_old - m_new) exactly as in Alg. 2, except
 // that A and B share one accumulator (they are only ever added).  Epilogue as in Alg. 2.
@@ -16,9 +16,11 @@
 namespace attn_jvp {
 namespace {
 
-constexpr int BR = 64;       // query rows per workgroup
 constexpr int BC = 32;       // key rows per tile
 constexpr int NTHREADS = 256;
+// lanes sharing one query row: 4 up to d = 128, 16 for d = 256 (keeps q, tq and the two accumulators of a lane at 64
+// registers; with 4 lanes the d = 256 kernel spilled and ran 14x slower per flop)
+constexpr int lanes_per_row(int d) { return d > 128 ? 16 : 4; }
 
 template <typename T> struct Ld;
 template <> struct Ld<float> {
@@ -49,7 +51,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
     const TIn* __restrict__ tQ, const TIn* __restrict__ tK, const TIn* __restrict__ tV,
     TOut* __restrict__ O, TOut* __restrict__ tO, float* __restrict__ LSE,
     int Lq, int Lkv, float scale, int H, int blhd) {
-    constexpr int NCH = D / 16;                 // float4 chunks per lane
+    constexpr int LPR = lanes_per_row(D);
+    constexpr int BR = NTHREADS / LPR;          // query rows per workgroup
+    constexpr int NCH = D / (4 * LPR);          // float4 chunks per lane
     extern __shared__ float4 smem[];            // 4 tiles of BC x D floats
     float4* sK = smem;
     float4* stK = sK + BC * D / 4;
@@ -57,8 +61,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
     float4* stV = sV + BC * D / 4;
 
     const int tid = threadIdx.x;
-    const int part = tid & 3;
-    const int row_in_blk = tid >> 2;
+    const int part = tid % LPR;
+    const int row_in_blk = tid / LPR;
     const long bh = blockIdx.y;
     const int q0 = blockIdx.x * BR;
     const int qrow = q0 + row_in_blk;
@@ -79,8 +83,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
     float4 q[NCH], tq[NCH], acc_o[NCH], acc_ab[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        q[c] = Ld<TIn>::load4(Qb + 4 * (part + 4 * c));
-        tq[c] = tQ ? Ld<TIn>::load4(tQb + 4 * (part + 4 * c)) : make_float4(0.f, 0.f, 0.f, 0.f);   // absent: zero
+        q[c] = Ld<TIn>::load4(Qb + 4 * (part + LPR * c));
+        tq[c] = tQ ? Ld<TIn>::load4(tQb + 4 * (part + LPR * c)) : make_float4(0.f, 0.f, 0.f, 0.f);   // absent: zero
         acc_o[c] = make_float4(0.f, 0.f, 0.f, 0.f);
         acc_ab[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -107,14 +111,14 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
             float a = 0.f, b = 0.f;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                float4 kk = sK[j * (D / 4) + part + 4 * c];
-                float4 tk = stK[j * (D / 4) + part + 4 * c];
+                float4 kk = sK[j * (D / 4) + part + LPR * c];
+                float4 tk = stK[j * (D / 4) + part + LPR * c];
                 a = fmaf(q[c].x, kk.x, a); a = fmaf(q[c].y, kk.y, a); a = fmaf(q[c].z, kk.z, a); a = fmaf(q[c].w, kk.w, a);
                 b = fmaf(tq[c].x, kk.x, b); b = fmaf(tq[c].y, kk.y, b); b = fmaf(tq[c].z, kk.z, b); b = fmaf(tq[c].w, kk.w, b);
                 b = fmaf(q[c].x, tk.x, b); b = fmaf(q[c].y, tk.y, b); b = fmaf(q[c].z, tk.z, b); b = fmaf(q[c].w, tk.w, b);
             }
-            a += __shfl_xor(a, 1); a += __shfl_xor(a, 2);
-            b += __shfl_xor(b, 1); b += __shfl_xor(b, 2);
+#pragma unroll
+            for (int o = 1; o < LPR; o <<= 1) { a += __shfl_xor(a, o); b += __shfl_xor(b, o); }
             bool valid = (j0 + j) < Lkv;
             s[j] = valid ? a * scale : -INFINITY;
             ts[j] = valid ? b * scale : 0.f;
@@ -136,8 +140,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
             row_h += h;
 #pragma unroll
             for (int c = 0; c < NCH; ++c) {
-                float4 vv = sV[j * (D / 4) + part + 4 * c];
-                float4 tv = stV[j * (D / 4) + part + 4 * c];
+                float4 vv = sV[j * (D / 4) + part + LPR * c];
+                float4 tv = stV[j * (D / 4) + part + LPR * c];
                 acc_o[c].x = fmaf(p, vv.x, acc_o[c].x); acc_o[c].y = fmaf(p, vv.y, acc_o[c].y);
                 acc_o[c].z = fmaf(p, vv.z, acc_o[c].z); acc_o[c].w = fmaf(p, vv.w, acc_o[c].w);
                 acc_ab[c].x = fmaf(p, tv.x, acc_ab[c].x); acc_ab[c].y = fmaf(p, tv.y, acc_ab[c].y);
@@ -162,8 +166,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
             t4.x = (ab.x - mu * o4.x) * inv_l; t4.y = (ab.y - mu * o4.y) * inv_l;
             t4.z = (ab.z - mu * o4.z) * inv_l; t4.w = (ab.w - mu * o4.w) * inv_l;
             o4.x *= inv_l; o4.y *= inv_l; o4.z *= inv_l; o4.w *= inv_l;
-            store4<TOut>(Ob + 4 * (part + 4 * c), o4);
-            if (tO) store4<TOut>(tOb + 4 * (part + 4 * c), t4);   // no tangent asked for: nothing to store
+            store4<TOut>(Ob + 4 * (part + LPR * c), o4);
+            if (tO) store4<TOut>(tOb + 4 * (part + LPR * c), t4);   // no tangent asked for: nothing to store
         }
         if (part == 0) LSE[bh * Lq + qrow] = m + logf(l);
     }
@@ -171,6 +175,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_fp32_kernel(
 
 template <typename TIn, typename TOut, int D>
 hipError_t launch_one(const Problem& p) {
+    constexpr int BR = NTHREADS / lanes_per_row(D);
     dim3 grid((p.Lq + BR - 1) / BR, p.B * p.H);
     size_t smem = 4ull * BC * D * sizeof(float);
     auto kern = attn_jvp_fp32_kernel<TIn, TOut, D>;
