@@ -69,9 +69,13 @@ extern "C" {
                                      lse stays [B, H, Lq]. */
 
 /* attn_jvp_opts.kernel */
-#define ATTN_JVP_KERNEL_AUTO 0    /* bf16, d=128, scale > 0 -> MFMA kernel; everything else -> fp32 vector kernel */
+#define ATTN_JVP_KERNEL_AUTO 0    /* bf16, scale > 0 and d = 128 (or d in {32, 64, 96} with a workspace) -> MFMA kernel;
+                                     everything else -> fp32 vector kernel */
 #define ATTN_JVP_KERNEL_FP32 1    /* fp32 vector-ALU streaming kernel: any dtype, d in {32, 64, 128, 256}, slow */
-#define ATTN_JVP_KERNEL_MFMA 2    /* bf16 matrix-core kernel: bf16 inputs, d = 128, scale > 0 */
+#define ATTN_JVP_KERNEL_MFMA 2    /* bf16 matrix-core kernel: bf16 inputs, scale > 0, d = 128; d in {32, 64, 96} given a workspace
+                                     of attn_jvp_workspace_bytes(...): the inputs are first copied there zero-padded to
+                                     128 columns (exact: the padding adds zeros to every product; half or more of the
+                                     matrix work is then spent on zeros) */
 
 /* attn_jvp_opts.flags */
 #define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only (not with absent tangents): round the weights P~ and H~ = P~ o tS to ONE bf16 term each
@@ -126,9 +130,10 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v,
                     const attn_jvp_opts* opts);
 
 /*
- * Bytes of scratch the fp16 value path of the MFMA kernel needs for this shape (0 if that path does not exist
- * for it): 2 fp16 copies of [B,H,Lkv,d], 32 bytes of statistics per (batch, head) and 4 bytes per 128-row query
- * tile, each part rounded up to 256 bytes.  Pure host arithmetic.
+ * Bytes of scratch the MFMA kernel can use for this shape (0 if it has no use for any).  d = 128: the fp16 value
+ * path's 2 fp16 copies of [B,H,Lkv,d], 32 bytes of statistics per (batch, head) and 4 bytes per 128-row query tile,
+ * each part rounded up to 256 bytes.  d in {32, 64, 96}: in front of that, zero-padded [.,128] bf16 copies of the
+ * six inputs (without them the MFMA kernel does not take these head dimensions).  Pure host arithmetic.
  */
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 

@@ -41,7 +41,7 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
               opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags,
               opts->workspace, opts->workspace ? opts->workspace_bytes : 0,
               static_cast<hipEvent_t>(opts->timing_events[0]), static_cast<hipEvent_t>(opts->timing_events[1]),
-              opts->layout};
+              opts->layout, d, opts->layout};
 
     int kernel = opts->kernel;
     if (kernel == ATTN_JVP_KERNEL_AUTO)
@@ -90,7 +90,10 @@ int attn_jvp_rmsnorm_fwd(const void* x, const void* tx, const float* w, void* y,
 }
 
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
-    if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0 || d != 128) return 0;
+    if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0) return 0;
+    if (d != 128 && d != 32 && d != 64 && d != 96) return 0;
+    if (d == 32 || d == 64 || d == 96)      // zero-padded copies of the inputs in front of the fp16 path's scratch
+        return attn_jvp::pad_workspace_bytes(B, H, Lq, Lkv) + attn_jvp::f16_workspace_bytes(B, H, Lq, Lkv, attn_jvp::MFMA_HEAD_DIM);
     return attn_jvp::f16_workspace_bytes(B, H, Lq, Lkv, d);
 }
 

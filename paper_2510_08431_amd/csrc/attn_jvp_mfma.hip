@@ -193,7 +193,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     void* __restrict__ O, void* __restrict__ tO, float* __restrict__ LSE,
     int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
-    int H, int blhd, int out_bf16) {
+    int H, int blhd, int out_bf16, int d_out, int out_blhd) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16;
     constexpr bool ZT = TAN != TAN_ALL;          // no key/value tangents
@@ -855,7 +855,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const float mu = r_row * inv_l;
     const float fo = gO * inv_l, ft = gAB * inv_l;
     if (qrow < Lq) {
-        const long out_off = q_base + (long)qrow * row_elems + 4 * g;
+        // Outputs: rows d_out elements wide in the caller's layout.  d_out = 128 unless the inputs are zero-padded
+        // copies of a smaller head dimension: then only the first d_out columns exist (and are stored).
+        const int o_row = out_blhd ? H * d_out : d_out;
+        const long o_base = out_blhd ? (bidx * Lq * H + hidx) * d_out : bh * (long)Lq * d_out;
+        const long out_off = o_base + (long)qrow * o_row + 4 * g;
         float* Op = static_cast<float*>(O) + out_off;
         float* tOp = static_cast<float*>(tO) + out_off;
         uint16_t* Ob = static_cast<uint16_t*>(O) + out_off;       // bf16 outputs: same element offsets
@@ -871,6 +875,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 t4.y = (accAB[db][4 * v4 + 1] - mu * a1) * ft;
                 t4.z = (accAB[db][4 * v4 + 2] - mu * a2) * ft;
                 t4.w = (accAB[db][4 * v4 + 3] - mu * a3) * ft;
+                if (32 * db + 8 * v4 >= d_out) continue;      // uniform: a column of the padding
                 if (out_bf16) {      // uniform; four bf16 = 8 bytes per lane and tensor
                     *reinterpret_cast<uint2*>(Ob + 32 * db + 8 * v4) = make_uint2(pack_bf16(o4.x, o4.y), pack_bf16(o4.z, o4.w));
                     if constexpr (!PRIMAL)
@@ -891,13 +896,24 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 // scale > 0: the kernel masks padded keys with a raw score of -inf and takes row maxima before scaling.
 // tk and tv are either both given or both absent (zero key/value tangents); single bf16 weights (FAST) are not built
 // for the latter.
+// Head dimensions 32, 64, 96: through zero-padded copies, which need the caller's workspace.
+static bool padded_head_dim(const Problem& p) {
+    return (p.d == 32 || p.d == 64 || p.d == 96) && p.workspace != nullptr &&
+           (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0 &&
+           p.workspace_bytes >= pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv);
+}
 bool mfma_bf16_supports(const Problem& p) {
     const bool zt = p.tk == nullptr && p.tv == nullptr;     // (the API admits absent tangents only as tk+tv or tq+tk+tv)
-    return p.in_dtype == 0 && p.d == D && p.scale > 0.f && !(zt && (p.flags & 1));
+    return p.in_dtype == 0 && (p.d == D || padded_head_dim(p)) && p.scale > 0.f && !(zt && (p.flags & 1));
 }
 
-hipError_t launch_mfma_bf16(const Problem& p) {
-    if (!mfma_bf16_supports(p)) return hipErrorInvalidValue;
+hipError_t launch_mfma_bf16(const Problem& p_in) {
+    if (!mfma_bf16_supports(p_in)) return hipErrorInvalidValue;
+    Problem p = p_in;
+    if (p_in.d != D) {      // run on zero-padded copies of the inputs; o, to keep the caller's width and layout
+        hipError_t e = launch_pad_inputs(p_in, &p);
+        if (e != hipSuccess) return e;
+    }
     const int q_tiles = (p.Lq + BR - 1) / BR;
     const long long blocks = (long long)q_tiles * p.B * p.H;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -908,7 +924,8 @@ hipError_t launch_mfma_bf16(const Problem& p) {
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
-                           p.o, p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout, p.out_dtype);
+                           p.o, p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout, p.out_dtype,
+                           p.d_out, p.out_layout);
         return hipGetLastError();
     };
     // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence

@@ -129,7 +129,68 @@ Layout layout(int B, int H, int Lq, int Lkv, int d) {
     auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
     return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)), up(heads * (size_t)Lkv * d * sizeof(__half))};
 }
+struct PadArgs {
+    const __hip_bfloat16* src[6];   // q, k, v, tq, tk, tv (null = absent)
+    __hip_bfloat16* dst[6];
+    int L[6];
+    int H, d, blhd;
+};
+
+// dst[B,H,L,128] = src rows (any layout) followed by zeros.  One thread per 16-byte chunk of dst; blockIdx.z = tensor.
+__global__ __launch_bounds__(256) void pad_inputs_kernel(PadArgs a, long heads) {
+    const int which = blockIdx.z;
+    if (a.src[which] == nullptr) return;
+    const int L = a.L[which];
+    const long n_chunks = heads * L * (D / 8);
+    for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n_chunks; i += (long)gridDim.x * blockDim.x) {
+        const int c = (int)(i % (D / 8));
+        const long hr = i / (D / 8);            // head * L + row
+        const long bh = hr / L;
+        const int row = (int)(hr % L);
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (c * 8 < a.d) {
+            const long src = a.blhd ? (((bh / a.H) * L + row) * a.H + bh % a.H) * (long)a.d : hr * (long)a.d;
+            v = *reinterpret_cast<const uint4*>(a.src[which] + src + c * 8);
+        }
+        *reinterpret_cast<uint4*>(a.dst[which] + i * 8) = v;
+    }
+}
+
 }  // namespace
+
+size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv) {
+    const size_t heads = (size_t)B * H;
+    auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
+    return 2 * up(heads * Lq * D * 2) + 4 * up(heads * Lkv * D * 2);
+}
+
+hipError_t launch_pad_inputs(const Problem& p, Problem* padded) {
+    const size_t heads = (size_t)p.B * p.H;
+    auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
+    const size_t qb = up(heads * p.Lq * D * 2), kb = up(heads * p.Lkv * D * 2);
+    char* ws = static_cast<char*>(p.workspace);
+    PadArgs a;
+    const void* srcs[6] = {p.q, p.k, p.v, p.tq, p.tk, p.tv};
+    const size_t offs[6] = {0, 2 * qb, 2 * qb + kb, qb, 2 * qb + 2 * kb, 2 * qb + 3 * kb};
+    for (int i = 0; i < 6; ++i) {
+        a.src[i] = static_cast<const __hip_bfloat16*>(srcs[i]);
+        a.dst[i] = reinterpret_cast<__hip_bfloat16*>(ws + offs[i]);
+        a.L[i] = (i == 0 || i == 3) ? p.Lq : p.Lkv;
+    }
+    a.H = p.H; a.d = p.d; a.blhd = p.layout;
+    const int Lmax = p.Lq > p.Lkv ? p.Lq : p.Lkv;
+    long blocks = ((long)heads * Lmax * (D / 8) + 255) / 256;
+    if (blocks > 8192) blocks = 8192;
+    hipLaunchKernelGGL(pad_inputs_kernel, dim3((unsigned)blocks, 1, 6), dim3(256), 0, p.stream, a, (long)heads);
+    *padded = p;
+    auto at = [&](int i) -> const void* { return srcs[i] ? static_cast<const void*>(a.dst[i]) : nullptr; };
+    padded->q = at(0); padded->k = at(1); padded->v = at(2); padded->tq = at(3); padded->tk = at(4); padded->tv = at(5);
+    padded->d = D;
+    padded->layout = 0;
+    padded->workspace = ws + pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv);
+    padded->workspace_bytes = p.workspace_bytes - pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv);
+    return hipGetLastError();
+}
 
 size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
     const Layout l = layout(B, H, Lq, Lkv, d);

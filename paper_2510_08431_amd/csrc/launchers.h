@@ -18,7 +18,9 @@ struct Problem {
     void* workspace;        // optional device scratch for the fp16 value path (may be null)
     size_t workspace_bytes;
     hipEvent_t ev_start, ev_stop;   // optional: recorded around the main kernel (may be null)
-    int layout;     // 0: q, k, v, tq, tk, tv, o, to are [B,H,L,d]; 1: they are [B,L,H,d].  lse is [B,H,Lq] either way
+    int layout;     // 0: q, k, v, tq, tk, tv are [B,H,L,d]; 1: they are [B,L,H,d].  lse is [B,H,Lq] either way
+    int d_out;      // width of the rows of o, to (= d, except when the inputs are zero-padded copies of a smaller d)
+    int out_layout; // layout of o, to (= layout, except for the same case)
 };
 
 // Records the caller's optional timing events around the main kernel's launch.
@@ -54,6 +56,13 @@ struct F16Workspace {
     const void* tv16;
 };
 size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
+
+// Head dimensions below 128 on the MFMA kernel: the inputs are first copied, zero-padded to 128 columns, into the
+// front of the workspace ([B,H,L,128] bf16 each, absent tangents skipped); the padded columns add exact zeros to
+// every product.  Bytes of that area, and the copy.
+constexpr int MFMA_HEAD_DIM = 128;
+size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv);
+hipError_t launch_pad_inputs(const Problem& p, Problem* padded);
 hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out);
 
 // RMS normalisation with gain + JVP over `rows` rows of length d

@@ -560,6 +560,55 @@ def test_mfma_bf16_outputs_are_the_rounded_fp32_outputs(variant):
     assert torch.equal(perm(ob), o16) and torch.equal(perm(tob), to16)
 
 
+# ------------------------------------------------------------------ head dimensions below 128 on the MFMA kernel
+
+@pytest.mark.parametrize("case", ["f16", "bf16-pairs", "fast", "pairs-null-kv", "no-tangents", "blhd-bf16-out", "default-long"])
+@pytest.mark.parametrize("d", [32, 64, 96])
+def test_mfma_small_head_dims_through_zero_padded_copies(d, case):
+    """d in {32, 64, 96}: given a workspace the MFMA kernel runs on copies of the inputs padded with zero columns to
+    128 (the padding adds exact zeros to every product) and stores only the first d columns."""
+    B, H, Lq, Lkv, flags, kw, null_kv, no_tan = 2, 2, 150, 333, 0, {}, False, False
+    if case == "f16":
+        flags = binding.FLAG_F16_ALWAYS
+    elif case == "bf16-pairs":
+        flags = binding.FLAG_NO_F16
+    elif case == "fast":
+        flags = binding.FLAG_FAST
+    elif case == "pairs-null-kv":
+        flags, null_kv = binding.FLAG_NO_F16, True
+    elif case == "no-tangents":
+        no_tan = True
+    elif case == "blhd-bf16-out":
+        kw = dict(layout=binding.LAYOUT_BLHD, out_dtype=torch.bfloat16)
+    elif case == "default-long":
+        B, H, Lq, Lkv = 1, 2, 130, 2300
+    t = random_inputs(1000 + d + len(case), B, H, Lq, Lkv, d, torch.bfloat16)
+    if null_kv:
+        t["tk"].zero_(); t["tv"].zero_()
+    prep = (lambda x: x.permute(0, 2, 1, 3).contiguous()) if "layout" in kw else (lambda x: x)
+    dev = {n: prep(x.to(DEV)) for n, x in t.items()}
+    tq, tk, tv = (None, None, None) if no_tan else (dev["tq"], None, None) if null_kv else (dev["tq"], dev["tk"], dev["tv"])
+    scale = d ** -0.5
+    o, to, lse = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], tq, tk, tv, scale,
+                                         kernel=binding.KERNEL_MFMA, flags=flags, **kw)
+    torch.cuda.synchronize()
+    assert tuple(o.shape) == tuple(dev["q"].shape)
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    back = lambda x: prep(x).float().cpu().double().numpy()
+    if no_tan:
+        assert to is None
+        e_o, e_lse = rel_err(back(o), ref[0]), float(np.abs(lse.cpu().double().numpy() - ref[2]).max())
+        print(f"[d={d} {case}] err O={e_o:.3e} lse={e_lse:.3e}", flush=True)
+        assert e_o <= TOL[torch.bfloat16][0] and e_lse <= TOL[torch.bfloat16][2]
+        return
+    tol = FAST_TOL if case == "fast" else (2e-2, 3e-2, 1e-3) if case == "blhd-bf16-out" else None
+    compare((back(o), back(to), lse.cpu().double().numpy()), ref, torch.bfloat16, f"d={d} {case}", tol=tol)
+    # without a workspace the MFMA kernel does not take this head dimension; AUTO then uses the vector kernel
+    with pytest.raises(binding.AttnJvpError):
+        binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], tq, tk, tv, scale, kernel=binding.KERNEL_MFMA,
+                                flags=flags, workspace=None, **kw)
+
+
 # ------------------------------------------------------------------ the five named configurations
 
 def check_config_sampled(cfg, n_random, heads=None):
