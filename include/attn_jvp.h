@@ -69,13 +69,16 @@ extern "C" {
                                      lse stays [B, H, Lq]. */
 
 /* attn_jvp_opts.kernel */
-#define ATTN_JVP_KERNEL_AUTO 0    /* bf16, scale > 0 and d = 128 (or d in {32, 64, 96} with a workspace) -> MFMA kernel;
-                                     everything else -> fp32 vector kernel */
+#define ATTN_JVP_KERNEL_AUTO 0    /* bf16, scale > 0 and d = 128 (or d in {32, 64, 96} with a workspace) -> bf16 MFMA kernel;
+                                     fp32 and d in {32, 64, 96, 128} -> fp32 MFMA kernel; everything else -> vector kernel */
 #define ATTN_JVP_KERNEL_FP32 1    /* fp32 vector-ALU streaming kernel: any dtype, d in {32, 64, 128, 256}, slow */
-#define ATTN_JVP_KERNEL_MFMA 2    /* bf16 matrix-core kernel: bf16 inputs, scale > 0, d = 128; d in {32, 64, 96} given a workspace
+#define ATTN_JVP_KERNEL_MFMA 2    /* matrix-core kernels.
+                                     bf16 inputs: scale > 0, d = 128; d in {32, 64, 96} given a workspace
                                      of attn_jvp_workspace_bytes(...): the inputs are first copied there zero-padded to
                                      128 columns (exact: the padding adds zeros to every product; half or more of the
-                                     matrix work is then spent on zeros) */
+                                     matrix work is then spent on zeros).
+                                     fp32 inputs: d in {32, 64, 96, 128}, any finite scale, fp32 outputs; fp32 operands
+                                     and fp32 accumulation throughout (Alg. 2 as printed), no workspace, flags ignored */
 
 /* attn_jvp_opts.flags */
 #define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only (not with absent tangents): round the weights P~ and H~ = P~ o tS to ONE bf16 term each

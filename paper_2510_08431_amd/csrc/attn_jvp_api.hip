@@ -43,14 +43,15 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
               static_cast<hipEvent_t>(opts->timing_events[0]), static_cast<hipEvent_t>(opts->timing_events[1]),
               opts->layout, d, opts->layout};
 
+    const bool f32 = opts->in_dtype == ATTN_JVP_FP32;
+    const bool mfma_ok = f32 ? attn_jvp::mfma_f32_supports(p) : attn_jvp::mfma_bf16_supports(p);
     int kernel = opts->kernel;
-    if (kernel == ATTN_JVP_KERNEL_AUTO)
-        kernel = attn_jvp::mfma_bf16_supports(p) ? ATTN_JVP_KERNEL_MFMA : ATTN_JVP_KERNEL_FP32;
+    if (kernel == ATTN_JVP_KERNEL_AUTO) kernel = mfma_ok ? ATTN_JVP_KERNEL_MFMA : ATTN_JVP_KERNEL_FP32;
 
     hipError_t e;
     if (kernel == ATTN_JVP_KERNEL_MFMA) {
-        if (!attn_jvp::mfma_bf16_supports(p)) return ATTN_JVP_UNSUPPORTED;
-        e = attn_jvp::launch_mfma_bf16(p);
+        if (!mfma_ok) return ATTN_JVP_UNSUPPORTED;
+        e = f32 ? attn_jvp::launch_mfma_f32(p) : attn_jvp::launch_mfma_bf16(p);
     } else if (kernel == ATTN_JVP_KERNEL_FP32) {
         if (!attn_jvp::fp32_vector_supports(p)) return ATTN_JVP_UNSUPPORTED;
         e = attn_jvp::launch_fp32_vector(p);

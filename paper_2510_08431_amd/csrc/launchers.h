@@ -41,7 +41,9 @@ struct MainKernelTimer {
 // (dtype, d) combination is not built for that kernel.
 hipError_t launch_fp32_vector(const Problem& p);
 hipError_t launch_mfma_bf16(const Problem& p);
+hipError_t launch_mfma_f32(const Problem& p);
 bool mfma_bf16_supports(const Problem& p);
+bool mfma_f32_supports(const Problem& p);
 bool fp32_vector_supports(const Problem& p);
 
 constexpr int MFMA_TILE_ROWS = 128;   // query rows per workgroup of the MFMA kernel

@@ -116,8 +116,8 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.workspace = 0x10010; o.workspace_bytes = 1 << 20   # workspace not 256-byte aligned
     assert _call(lib, opts=o) == 4
-    o = AttnJvpOpts(); o.kernel = 2; o.in_dtype = 1        # MFMA kernel with fp32 inputs
-    assert _call(lib, opts=o) == 3
+    o = AttnJvpOpts(); o.kernel = 2; o.in_dtype = 1        # MFMA kernels with fp32 inputs: d in {32, 64, 96, 128} only
+    assert _call(lib, dims=(1, 1, 8, 8, 256), opts=o) == 3
     o = AttnJvpOpts(); o.kernel = 2                        # MFMA kernel with d = 64
     assert _call(lib, dims=(1, 1, 8, 8, 64), opts=o) == 3
     for bad_scale in (0.0, -0.125):                        # MFMA kernel needs scale > 0 (AUTO then takes the fp32 kernel)
