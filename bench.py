@@ -19,6 +19,7 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6   # MI355X dense bf16 MFMA: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 
 
+PEAK_FP32_TFLOPS = 157.3     # MI355X dense fp32 MFMA
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 
 
@@ -100,6 +101,9 @@ def main():
                          "the kernel then executes 8*Lq*Lkv*d flop per head, the metric still counts 12")
     ap.add_argument("--layout", choices=["bhld", "blhd"], default="bhld",
                     help="memory layout of the eight tensors: [B,H,L,d] (default) or [B,L,H,d]")
+    ap.add_argument("--input-dtype", choices=["config", "fp32"], default="config",
+                    help="fp32: hold the workload's inputs (the same values) in fp32, which takes the fp32 matrix-core kernel; "
+                         "priced against the fp32 MFMA peak")
     ap.add_argument("--op", choices=["attention", "rmsnorm"], default="attention",
                     help="attention (default: the headline metric) or rmsnorm: the RMSNorm + JVP kernel on the q tensor "
                          "of the chosen workload (its QK-normalisation), an HBM-bound second workload with its own line")
@@ -139,6 +143,10 @@ def main():
         return
     t = {n: x.to(dev) for n, x in make_inputs(cfg).items()}
     B, H, Lq, Lkv, d = cfg.B, cfg.H, cfg.Lq, cfg.Lkv, cfg.d
+    f32 = cfg.dtype != "bf16" or args.input_dtype == "fp32"
+    if f32:
+        t = {n: x.float() for n, x in t.items()}
+    workload = cfg.name + ("-as-fp32" if f32 and cfg.dtype == "bf16" else "")
     layout = binding.LAYOUT_BHLD
     if args.layout == "blhd":
         t = {n: x.permute(0, 2, 1, 3).contiguous() for n, x in t.items()}
@@ -183,21 +191,27 @@ def main():
     traffic = None
     try:
         with open(args.traffic_json) as f:
-            traffic = json.load(f).get(cfg.name)
+            traffic = json.load(f).get(workload)
     except OSError:
         pass
 
+    peak = PEAK_FP32_TFLOPS if f32 else PEAK_BF16_TFLOPS
+    if f32:
+        kernel_name = "attn_jvp_mfma_f32_kernel" if d in (32, 64, 96, 128) else "attn_jvp_fp32_kernel"
+    else:
+        kernel_name = "attn_jvp_mfma_kernel" if d in (32, 64, 96, 128) and cfg.scale > 0 else "attn_jvp_fp32_kernel"
     out = {
-        "metric": "attention+JVP TFLOP/s (bf16, 12*Lq*Lkv*d/head)", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "metric": f"attention+JVP TFLOP/s ({'fp32' if f32 else 'bf16'}, 12*Lq*Lkv*d/head)", "value": round(tflops, 2),
+        "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
+        "dtype": "f32" if f32 else "bf16", "data": "synthetic",
+        "config": {"workload": workload, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
                    "variant": args.variant, "kv_tangents": "null" if args.null_kv_tangents else "tensors", "layout": args.layout},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
-        "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(kern_tflops / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                     "kernel": "attn_jvp_mfma_kernel" if cfg.dtype == "bf16" and d == 128 else "attn_jvp_fp32_kernel",
+        "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": peak, "unit": "TFLOP/s",
+                     "frac": round(kern_tflops / peak, 4), "traffic": traffic,
+                     "kernel": kernel_name,
                      "kernel_ms_avg": round(kern_avg_ms, 4), "kernel_ms_min": round(float(np.min(kern_ms)), 4),
                      "kernel_ms_median": round(float(np.median(kern_ms)), 4)},
     }
@@ -207,8 +221,8 @@ def main():
         # (all keys) of the first few heads, sized for roughly 10-20 s of host work
         from oracle.attn_jvp_ref import attn_jvp_ref
         rows_per_head = min(Lq, max(16, int(5.0e11 / (12.0 * Lkv * d))))
-        n_heads = min(B * H, 6)
         rows = sample_rows(cfg, rows_per_head)[:rows_per_head]
+        n_heads = min(B * H, max(6, int(5.0e11 / (12.0 * len(rows) * Lkv * d))))     # short sequences: more heads
         heads = [{n: x[None, None] for n, x in make_head(cfg, i // H, i % H).items()} for i in range(n_heads)]
         attn_jvp_ref(*(heads[0][n] for n in ("q", "k", "v", "tq", "tk", "tv")), cfg.scale, rows=rows[:8])
         c0 = time.perf_counter()

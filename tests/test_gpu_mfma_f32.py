@@ -99,8 +99,9 @@ def test_query_lengths_around_tile_edges():
 
 @pytest.mark.parametrize("gain", [3.0, 6.0])
 def test_peaked_softmax_takes_the_rescale_path(gain):
-    """Scores with a standard deviation of 9 and 36 nats: the running maximum moves in most blocks, so the
-    accumulators are rescaled again and again, and single keys dominate rows (the cancelling terms of tO).
+    """Scores with a standard deviation of 9 and 36 nats: single keys dominate rows (the cancelling terms of tO), and
+    at 36 nats a block's maximum often exceeds the row reference by more than its 32 nats of slack, so that the
+    accumulators are rescaled again and again.
     An fp32 score of size |S| carries an absolute error of a few 2^-24 |S| (its 128-term fp32 dot product), which the
     exponential turns into a relative error of the weights; with one key dominating a row nothing averages it out.
     Measured on these inputs: 6 to 20 times 2^-24 max|S| for O, tO and lse (3 to 6 times in the fp32 vector kernel,
@@ -112,16 +113,19 @@ def test_peaked_softmax_takes_the_rescale_path(gain):
             extra_tol=40 * 2.0 ** -24 * s_max)
 
 
-def test_increasing_scores_rescale_in_every_block():
-    """Keys ordered so that, for every query, each block's scores exceed the previous block's by about 3 nats: the
-    running maximum moves and the accumulators are rescaled in every block (the extra tolerance as in the peaked case)."""
+@pytest.mark.parametrize("step", [0.05, 0.25])
+def test_increasing_scores(step):
+    """Keys ordered so that every query's scores grow along the sequence, by 2 * step nats per key.  The kernel's
+    row reference trails the row maximum by up to 32 nats: at 0.1 nat per key the weights climb to e^32 before the
+    first move of the reference near the end; at 0.5 nat per key the reference moves, and the accumulators are
+    rescaled, every other block (the extra tolerance as in the peaked case)."""
     d, Lq, Lkv = 64, 64, 320
     g = torch.Generator().manual_seed(5)
     u = torch.randn(d, generator=g)
     u /= u.norm()
     t = random_inputs(6, 1, 1, Lq, Lkv, d)
     t["q"] = 0.3 * t["q"] + 2.0 * u                                   # every query points along u
-    t["k"] = 0.3 * t["k"] + torch.arange(Lkv).view(1, 1, Lkv, 1) * 0.05 * u   # keys grow along u: 0.1 nat per key
+    t["k"] = 0.3 * t["k"] + torch.arange(Lkv).view(1, 1, Lkv, 1) * step * u   # keys grow along u
     s_max = float((t["q"].double() @ t["k"].double().transpose(-1, -2)).abs().max())
     compare(to_np(run(t, 1.0)), oracle(t, 1.0), f"mfma-f32 increasing scores max|S|={s_max:.0f}", Lkv,
             extra_tol=40 * 2.0 ** -24 * s_max)
