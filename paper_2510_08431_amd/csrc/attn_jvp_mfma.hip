@@ -71,6 +71,16 @@ static_assert(PRESCAN_BLOCKS >= 2 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES 
 // nothing may be scheduled across a fence: the instruction order between fences is the issue order
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
 #define MFMA(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+// Score products of the main loop, with the result in ARITHMETIC registers.  The vector ALU reads every score, and
+// the compiler, once a kernel uses accumulation registers at all, places every MFMA result there: 32 single-register
+// copies per key block to get the scores out.  Written as assembly, the MFMA delivers them where they are needed.
+// The compiler does not see inside: it still orders the LDS reads that produce operand `a` (they are register
+// operands of the statement), but it knows nothing of the 11 wait states an 8-pass MFMA needs before the vector ALU
+// may read its result; the loop provides them itself (SCORE_RESULTS_LAND) after the last score product of a block.
+// `b` (a Q or tQ fragment) lives in accumulation registers.  SMFMA0 starts a chain (C = 0), SMFMA continues it.
+#define SMFMA0(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b))
+#define SMFMA(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b))
+#define SCORE_RESULTS_LAND() asm volatile("s_nop 7\n\ts_nop 3" ::: "memory")     // 12 wait states
 // value contractions: bf16 or fp16 operands (the fragments are carried as raw 128-bit registers)
 #define VMFMA(a, b, c)                                                                                          \
     (F16 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0) \
@@ -629,23 +639,21 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         using K2 = std::integral_constant<int, (U + 2) & 3>;    // K stage of block b+2
         using V0 = std::integral_constant<int, U>;              // V stage of block b
         f32x16 s, ts;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
         // ---- phase 1
         static_for<8>([&](auto T) {
             constexpr int t = decltype(T)::value;
             using J = std::integral_constant<int, 4 + t / 2>;
             constexpr int s0 = (t % 2) * PRODUCTS;
-            s = MFMA(kfr[t % KRING], qf[t], s);
+            if constexpr (t == 0) SMFMA0(kfr[t % KRING], qf[t], s); else SMFMA(kfr[t % KRING], qf[t], s);
             softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{});
             FENCE();
             if constexpr (!PRIMAL) {
-                ts = MFMA(kfr[t % KRING], tqf[t], ts);
+                if constexpr (t == 0) SMFMA0(kfr[t % KRING], tqf[t], ts); else SMFMA(kfr[t % KRING], tqf[t], ts);
                 softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{});
                 FENCE();
             }
             if constexpr (!ZT) {
-                ts = MFMA(tkfr[t % KRING], qf[t], ts);
+                SMFMA(tkfr[t % KRING], qf[t], ts);
                 softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{});
                 FENCE();
             }
@@ -654,6 +662,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             FENCE();
         });
         // ---- middle
+        SCORE_RESULTS_LAND();
         // all but the newest copies (8 instructions per wave and iteration, 4 without tangents) landed: K(b+2), V(b+1) are in
         if constexpr (ZT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");

@@ -241,7 +241,14 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_mfma_f32_kernel(
                 }
                 FENCE();
             }
-            if constexpr (TAN == TAN_ALL) ts += ts2;
+            // the vector ALU reads the scores next: have the MFMAs deliver them in arithmetic registers (left alone, the
+            // compiler puts them in accumulation registers and copies all 48 out, one instruction each)
+            asm volatile("" : "+v"(s));
+            if constexpr (TAN != TAN_NONE) asm volatile("" : "+v"(ts));
+            if constexpr (TAN == TAN_ALL) {
+                asm volatile("" : "+v"(ts2));
+                ts += ts2;
+            }
         }
         // ---- online softmax of Alg. 2 on this lane's 16 keys: register e holds key j0 + 8(e/4) + 4h + e%4 -----------
         // The running maximum m is a reference, not a result: it is taken over the rounded products S scale, and the
