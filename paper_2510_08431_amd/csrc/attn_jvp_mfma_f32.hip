@@ -82,7 +82,7 @@ __device__ __forceinline__ f32x16 mfma(float a, float b, f32x16 c) {
 }
 
 template <int D, int TAN>
-__global__ __launch_bounds__(NTHREADS) void attn_jvp_mfma_f32_kernel(
+__global__ __launch_bounds__(NTHREADS, D <= 64 ? 2 : 1) void attn_jvp_mfma_f32_kernel(
     const float* __restrict__ Q, const float* __restrict__ K, const float* __restrict__ V,
     const float* __restrict__ tQ, const float* __restrict__ tK, const float* __restrict__ tV,
     float* __restrict__ O, float* __restrict__ tO, float* __restrict__ LSE,
@@ -200,6 +200,9 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_mfma_f32_kernel(
         // Three independent accumulation chains (S, K tQ^T, tK Q^T), issued round-robin so that no MFMA waits for the
         // one before it; the operands of step u + 1 are read from LDS while the 12 MFMAs of step u run (the fences
         // keep the compiler from sinking the reads down to their first use).
+        // (up to d = 64 two workgroups share a CU and each wave has 256 registers: there tS is one chain, and the
+        // other workgroup's waves fill the gaps)
+        constexpr bool THREE_CHAINS = D > 64;
         f32x16 s = f32x16{}, ts = f32x16{}, ts2 = f32x16{};
         {
             // chunk (2u + h) ^ (j & 7) = 8 (u/4) + ((2 (u%4) + h) ^ (j & 7)): four lane-dependent addresses, the rest
@@ -236,7 +239,8 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_mfma_f32_kernel(
                     }
                     if constexpr (TAN == TAN_ALL) {
                         const float tkv[4] = {tka[u & 1].x, tka[u & 1].y, tka[u & 1].z, tka[u & 1].w};
-                        ts2 = mfma(tkv[e], qv[e], ts2);
+                        if constexpr (THREE_CHAINS) ts2 = mfma(tkv[e], qv[e], ts2);
+                        else ts = mfma(tkv[e], qv[e], ts);
                     }
                 }
                 FENCE();
@@ -245,7 +249,7 @@ __global__ __launch_bounds__(NTHREADS) void attn_jvp_mfma_f32_kernel(
             // compiler puts them in accumulation registers and copies all 48 out, one instruction each)
             asm volatile("" : "+v"(s));
             if constexpr (TAN != TAN_NONE) asm volatile("" : "+v"(ts));
-            if constexpr (TAN == TAN_ALL) {
+            if constexpr (TAN == TAN_ALL && THREE_CHAINS) {
                 asm volatile("" : "+v"(ts2));
                 ts += ts2;
             }
