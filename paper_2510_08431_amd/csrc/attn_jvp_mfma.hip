@@ -77,6 +77,10 @@ static_assert(PRESCAN_BLOCKS >= 2 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES 
 // The compiler does not see inside: it still orders the LDS reads that produce operand `a` (they are register
 // operands of the statement), but it knows nothing of the 11 wait states an 8-pass MFMA needs before the vector ALU
 // may read its result; the loop provides them itself (SCORE_RESULTS_LAND) after the last score product of a block.
+// Nor does it know that the result registers are busy until then: a result lane nobody reads later would be handed
+// to the next LDS load at once, which the MFMA would then overwrite.  Every lane of s and ts is therefore read
+// through a pinned copy after the wait (the hand-over in phase 2), and the build checks the compiled assembly for
+// both kinds of accident (lint_mfma_asm.py).
 // `b` (a Q or tQ fragment) lives in accumulation registers.  SMFMA0 starts a chain (C = 0), SMFMA continues it.
 #define SMFMA0(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b))
 #define SMFMA(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b))
