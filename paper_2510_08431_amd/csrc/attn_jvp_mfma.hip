@@ -194,7 +194,10 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int
 // ZT ("zero key/value tangents", cross-attention onto a context that does not depend on the differentiated
 // variable; template value TAN_QUERY): tK = tV = 0 are not passed at all.  tS = scale tQ K^T and tO = tP V then need 4 of the 6 products, and
 // only K and V are streamed; the stage layout stays the same, the tangent halves are simply never written or read.
-constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2;
+constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2, MODE_F16_ONLINE = 3;
+// MODE_F16_ONLINE: fp16 weights as MODE_F16, but the exponent reference follows the running row maximum (Alg. 2's
+// rescaling, done lazily) instead of being fixed from a sample: the tier for the tiles MODE_F16 declines or abandons.
+constexpr float ONLINE_SLACK = 4.f;   // binades by which a block's maximum may exceed the running one before m moves
 constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
 // TAN selects which tangents exist: TAN_ALL (tQ, tK, tV), TAN_QUERY (tQ only: "ZT" below, zero key/value tangents)
@@ -209,14 +212,23 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
     int H, int blhd, int out_bf16, int d_out, int out_blhd) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
-    constexpr bool F16 = MODE == MODE_F16;
+    constexpr bool F16 = MODE == MODE_F16 || MODE == MODE_F16_ONLINE;   // fp16 weights and value operands
+    constexpr bool PRESCAN = MODE == MODE_F16;                          // fixed reference from a key sample
+    constexpr bool ONLINE = MODE == MODE_F16_ONLINE;                    // reference follows the running maximum
+    // The online tier gets the peaked rows, where a few keys carry a row and the 11 bits of their H~ survive the
+    // B - r O cancellation (measured 1.5e-2 of the 2e-2 allowed on the stress workload): there H~ enters the V
+    // product as hi + lo fp16 terms, one product more (7 per key block).
+    constexpr bool HSPLIT = ONLINE && TAN != TAN_NONE;
     constexpr bool ZT = TAN != TAN_ALL;          // no key/value tangents
     constexpr bool PRIMAL = TAN == TAN_NONE;     // no tangents at all
-    // Hand-over between the fp16 launch and the bf16-pair launch that follows it on the same stream: the fp16
-    // kernel writes wg_flags[workgroup] = 1 for every tile it declines or abandons (and 0 otherwise) and stores
-    // nothing for those; the pair kernel, given the flags, works on exactly those tiles.
-    if constexpr (!F16) {
-        if (wg_flags != nullptr && wg_flags[blockIdx.x] == 0) return;
+    // Hand-over between the launches of the fp16 path, which follow each other on one stream: the fp16 kernel
+    // writes wg_flags[workgroup] = 1 for every tile it declines or abandons (0 otherwise) and stores nothing for
+    // those; the online fp16 kernel works on exactly the tiles flagged 1 and sets 3 (done), or 2 if it has to
+    // abandon one itself; the bf16-pair kernel, given the flags, works on exactly the tiles flagged 2.
+    if constexpr (ONLINE) {
+        if (wg_flags[blockIdx.x] != 1) return;
+    } else if constexpr (!F16) {
+        if (wg_flags != nullptr && wg_flags[blockIdx.x] != 2) return;
     }
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
@@ -271,7 +283,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     auto sample_block = [&](int i) -> int {
         return n_blocks <= PRESCAN_BLOCKS ? i : (int)(((long)i * (n_blocks - 1)) / (PRESCAN_BLOCKS - 1));
     };
-    if constexpr (F16) {
+    if constexpr (PRESCAN) {
         for (int i = 0; i < ns; ++i) {
             const int blk = sample_block(i);
 #pragma unroll
@@ -341,7 +353,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     float ctr_h;              // gH * ctr, ctr = per-row centre subtracted from the scaled tangent scores
 
     uint32_t wp[8], wh[8];                              // P~^T, H~^T as packed bf16 pairs, result-register order
-    uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT ? 8 : 1];    // their low-order parts
+    uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT || HSPLIT ? 8 : 1];    // their low-order parts
 
     float sv[16], tsv[16];    // scores of the block whose softmax comes next, in ordinary registers
 
@@ -372,6 +384,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             wh[j] = hh;
             if constexpr (SPLIT)
                 whl[j] = pack_bf16(sh0 - __uint_as_float(hh << 16), sh1 - __uint_as_float(hh & 0xffff0000u));
+            if constexpr (HSPLIT) {
+                const f32x2 hi = __builtin_convertvector(__builtin_bit_cast(f16x2, hh), f32x2);
+                whl[j] = pack_f16(sh0 - hi[0], sh1 - hi[1]);
+            }
         }
     };
     auto softmax_pair = [&](auto J) __attribute__((always_inline)) {
@@ -448,6 +464,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 accO[db] = VMFMA(vf, pb, accO[db]);
                 if constexpr (!ZT) accAB[db] = VMFMA(tvf, pb, accAB[db]);
                 if constexpr (!PRIMAL) accAB[db] = VMFMA(vf, hb8, accAB[db]);
+                if constexpr (HSPLIT)
+                    accAB[db] = VMFMA(vf, as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]), accAB[db]);
                 if constexpr (SPLIT) {
                     const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                     accO[db] = VMFMA(vf, pl8, accO[db]);
@@ -470,11 +488,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     //   fp16 weights: H~ (up to 2^8 P~ after scaling) must stay below 2^16 and the weights that carry the sum
     //   (some 5 binades below the largest) above 2^-14, so m has to be close to the true maximum:
     //   m = maximum over a sample of ~16 evenly spaced key blocks (first and last included) + 6 binades.
-    constexpr float REF_HEADROOM = F16 ? 6.f : 40.f;
+    //   fp16 weights, online: m = running maximum - 3 binades, moved (with a rescale of everything accumulated)
+    //   when a block's maximum exceeds the running one by more than ONLINE_SLACK: weights stay below 2^7.
+    constexpr float REF_HEADROOM = PRESCAN ? 6.f : ONLINE ? -3.f : 40.f;
     constexpr float F16_MAX_GAP = 13.f;
     float headroom = REF_HEADROOM;
     float m_scan = -INFINITY;
-    if constexpr (F16) {
+    if constexpr (PRESCAN) {
         float sum1 = 0.f, sum2 = 0.f;   // first and second moment of the sampled raw scores (full blocks only)
         int n_stat = 0;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -559,7 +579,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         __syncthreads();
         plain_scores(0);
         if (n_blocks == 1) mask_scores(0);
-        m = (F16 ? m_scan : row_max()) + REF_HEADROOM;
+        m = (PRESCAN ? m_scan : row_max()) + REF_HEADROOM;
         float lb = 0.f, rb = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -573,6 +593,59 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         r_part = 0.f;
         static_for<4>([&](auto J) { softmax_pair(J); });   // pairs 0-3 of block 0; pairs 4-7 follow in iteration 0
     }
+
+    // ---- online reference (MODE_F16_ONLINE).  Checked once per block, when the scores of block b+1 have been handed
+    // over (middle of iteration b's phase 2).  If a row's block maximum exceeds its running maximum by more than the
+    // slack, that row's reference moves there, and with it the tangent-score centre moves to the running value of
+    // rowsum(P o tS) (a dominant key has appeared: centring on it keeps its H~ small and exactly representable):
+    // Alg. 2's rescale, plus B <- B - (ctr_new - ctr_old) O~ as in the safe sweep.  l and r are complete up to block
+    // b at that point and are rescaled at once; the accumulators still receive the rest of block b, weighted in the
+    // old frame, and are rescaled at the end of the iteration.  Rare: a cold path.
+    bool pend = false;
+    float pend_alpha = 1.f, pend_da = 0.f;
+    auto online_check = [&]() __attribute__((always_inline)) {
+        const float mb = row_max();
+        const bool upd = mb > (m - REF_HEADROOM) + ONLINE_SLACK;
+        if (__builtin_expect(__builtin_amdgcn_ballot_w64(upd) != 0, 0)) {
+            const float m_new = upd ? mb + REF_HEADROOM : m;
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+            float lb = 0.f, rb = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m_new));
+                lb += pe;
+                if constexpr (!PRIMAL) rb = fmaf(pe, fmaf(tsv[e], scale_h, -ctr_h), rb);
+            }
+            l_part *= alpha;
+            r_part *= alpha;
+            const float l_row = xhalf_sum(l_part + lb);
+            const float r_row = xhalf_sum(r_part + rb);
+            const float delta = upd ? r_row / l_row : 0.f;      // gH * (running rowsum(P o tS) minus ctr)
+            ctr_h += delta;
+            r_part = fmaf(-delta, l_part, r_part);
+            pend_alpha = alpha;
+            pend_da = delta * alpha;
+            pend = true;
+            m = m_new;
+        }
+    };
+    auto online_apply = [&]() __attribute__((always_inline)) {
+        if (__builtin_expect(pend, 0)) {
+            // (the empty statements tie the accumulators to the accumulation registers on entry and exit, so that
+            // the copies to and from arithmetic registers stay inside this block)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                asm volatile("" : "+a"(accO[db]), "+a"(accAB[db]));
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    if constexpr (!PRIMAL) accAB[db][e] = fmaf(accAB[db][e], pend_alpha, -pend_da * accO[db][e]);
+                    accO[db][e] *= pend_alpha;
+                }
+                asm volatile("" : "+a"(accO[db]), "+a"(accAB[db]));
+            }
+            pend = false;
+        }
+    };
 
     // ---- pipelined sweep.  Iteration b (U = b & 3 selects the ring stages at compile time):
     //   phase 1: score MFMAs of block b+1, block b's softmax arithmetic underneath;
@@ -636,7 +709,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         constexpr int U = decltype(Uc)::value;
         constexpr bool FULL = decltype(FULLc)::value;
         constexpr int PRODUCTS = PRIMAL ? 1 : ZT ? 2 : 3;         // matrix products per score step / per weight term
-        constexpr int GROUP_MFMAS = SPLIT ? 2 * PRODUCTS : PRODUCTS;
+        constexpr int GROUP_MFMAS = SPLIT ? 2 * PRODUCTS : HSPLIT ? PRODUCTS + 1 : PRODUCTS;
         using NS_P1 = std::integral_constant<int, 2 * PRODUCTS>;  // phase 1: two score steps per pair
         using NS_P2 = std::integral_constant<int, GROUP_MFMAS>;   // phase 2: one value group per pair
         using K1 = std::integral_constant<int, (U + 1) & 3>;    // K stage of block b+1
@@ -682,6 +755,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 // tail iterations only: keys past Lkv (a ragged last block, or the unused block past the end)
                 if ((b + 2) * BC > Lkv) mask_scores(b + 1);
             }
+            if constexpr (gi == 4 && ONLINE) online_check();
             const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
             bf16x8 hb8 = pb;
             if constexpr (!PRIMAL) hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
@@ -723,6 +797,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 accAB[db] = VMFMA(vfr[gi % VRING], hb8, accAB[db]);
                 behind(std::integral_constant<int, PRODUCTS - 1>{});
             }
+            if constexpr (HSPLIT) {
+                const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
+                FENCE();
+                accAB[db] = VMFMA(vfr[gi % VRING], hl8, accAB[db]);
+                behind(std::integral_constant<int, PRODUCTS>{});
+            }
             if constexpr (SPLIT) {
                 const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                 FENCE();
@@ -746,6 +826,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             if constexpr (gi >= KFIRST && gi < KFIRST + KPRE) read_k(std::integral_constant<int, gi - KFIRST>{}, K2{});
             FENCE();
         });
+        if constexpr (ONLINE) online_apply();     // block b is complete: move the accumulators to the new frame, if any
     };
 
     {
@@ -807,8 +888,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         const bool redo = *flag != 0;
         __syncthreads();
         if constexpr (F16) {
-            // the fp16 kernel does not repair: it hands the tile to the bf16-pair launch that follows
-            if (threadIdx.x == 0) wg_flags[blockIdx.x] = redo ? 1 : 0;
+            // the fp16 kernels do not repair: they hand the tile to the launch that follows (online fp16, then bf16 pairs)
+            if (threadIdx.x == 0) wg_flags[blockIdx.x] = redo ? (ONLINE ? 2 : 1) : (ONLINE ? 3 : 0);
             if (redo) return;
         } else if (__builtin_expect(redo, 0)) {
             // ============================ safe sweep (rare) ============================
@@ -954,30 +1035,26 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     }
     MainKernelTimer timer(p);
     hipError_t e;
+    // fp16 path: every tile is finished by exactly one of three launches.  The fp16 kernel with its sampled, fixed
+    // reference flags the tiles it declines (scores too spread out) or abandons (overflow found at the end of its
+    // sweep); the online fp16 kernel does those, unless it meets an overflow itself (tangent scores beyond the fp16
+    // range), which it flags for the bf16-pair kernel; each returns at once from the tiles that are not its own.
+    auto run = [&](auto tan, const void* tv, const void* tv16) -> hipError_t {
+        constexpr int T = decltype(tan)::value;
+        if (!f16) return launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T>, p.v, tv, nullptr, nullptr);
+        hipError_t err = launch(attn_jvp_mfma_kernel<MODE_F16, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
+        if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_F16_ONLINE, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
+        if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T>, p.v, tv, nullptr, ws.wg_flags);
+        return err;
+    };
     if (p.tq == nullptr) {             // no tangents at all: plain attention forward
-        if (f16) {
-            e = launch(attn_jvp_mfma_kernel<MODE_F16, TAN_NONE>, ws.v16, nullptr, ws.stats, ws.wg_flags);
-            if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_NONE>, p.v, nullptr, nullptr, ws.wg_flags);
-        } else {
-            e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_NONE>, p.v, nullptr, nullptr, nullptr);
-        }
+        e = run(std::integral_constant<int, TAN_NONE>{}, nullptr, nullptr);
     } else if (p.tk == nullptr) {      // zero key/value tangents
-        if (f16) {
-            e = launch(attn_jvp_mfma_kernel<MODE_F16, TAN_QUERY>, ws.v16, nullptr, ws.stats, ws.wg_flags);
-            if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_QUERY>, p.v, nullptr, nullptr, ws.wg_flags);
-        } else {
-            e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_QUERY>, p.v, nullptr, nullptr, nullptr);
-        }
+        e = run(std::integral_constant<int, TAN_QUERY>{}, nullptr, nullptr);
     } else if (p.flags & 1) {
         e = launch(attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL>, p.v, p.tv, nullptr, nullptr);
-    } else if (f16) {
-        // every tile is finished by exactly one of the two launches: the fp16 kernel flags the tiles it declines
-        // (scores too spread out for fp16 weights) or abandons (overflow found at the end of its sweep), the
-        // bf16-pair kernel does those and returns at once from the others
-        e = launch(attn_jvp_mfma_kernel<MODE_F16, TAN_ALL>, ws.v16, ws.tv16, ws.stats, ws.wg_flags);
-        if (e == hipSuccess) e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_ALL>, p.v, p.tv, nullptr, ws.wg_flags);
     } else {
-        e = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_ALL>, p.v, p.tv, nullptr, nullptr);
+        e = run(std::integral_constant<int, TAN_ALL>{}, p.tv, ws.tv16);
     }
     return timer.finish(e);
 }

@@ -224,7 +224,8 @@ def test_mfma_peaked_softmax_small():
 
 def f16_tile_flags(B, H, Lq):
     """Hand-over flags the last fp16-path call left in the binding's cached workspace (one int per 128-row query
-    tile, after the per-head statistics): 1 = tile done by the bf16-pair launch, 0 = done by the fp16 launch."""
+    tile, after the per-head statistics): 0 = tile done by the fp16 launch with the sampled reference, 3 = by the
+    online fp16 launch, 2 = by the bf16-pair launch."""
     ws = binding._workspaces[(torch.device(DEV), torch.cuda.current_stream(DEV).cuda_stream)]
     off = (B * H * 32 + 255) // 256 * 256
     n = B * H * ((Lq + 127) // 128)
@@ -238,8 +239,9 @@ def f16_tile_flags(B, H, Lq):
 
 
 def test_f16_path_routes_tiles_by_score_spread():
-    """Head 0 has N(0,1) logits (fp16 weights are fine), head 1 logits of std ~8 (sampled maximum unreliable):
-    the fp16 launch must keep the first and hand the second to the bf16-pair launch; both within tolerance."""
+    """Head 0 has N(0,1) logits (a sampled, fixed reference is fine), head 1 logits of std ~8 (sampled maximum
+    unreliable): the first fp16 launch must keep the first and hand the second to the online fp16 launch; both
+    within tolerance."""
     B, H, Lq, Lkv = 1, 2, 384, 4096
     t = random_inputs(51, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
     t["q"][:, 1] *= 8 ** 0.5
@@ -247,20 +249,20 @@ def test_f16_path_routes_tiles_by_score_spread():
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "mixed heads, f16 path")
     flags = f16_tile_flags(B, H, Lq)
     print("[tile flags]", flags.tolist(), flush=True)
-    assert (flags[0] == 0).all() and (flags[1] == 1).all()
+    assert (flags[0] == 0).all() and (flags[1] == 3).all()
 
 
 def test_f16_path_abandons_tiles_that_overflow():
     """One key outside the sampled blocks (key 33; the sample takes every 8th block of 128) scores far above the
     sampled maximum for about half of the queries: the sample statistics look harmless, the fp16 weights
-    overflow, the end-of-sweep check must notice and the bf16-pair launch must redo those tiles."""
+    overflow, the end-of-sweep check must notice and the online fp16 launch must redo those tiles."""
     B, H, Lq, Lkv = 1, 1, 512, 4096
     t = random_inputs(52, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
     t["k"][:, :, 33] *= 24.0
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "outlier key missed by the sample, f16 path")
     flags = f16_tile_flags(B, H, Lq)
     print("[tile flags]", flags.tolist(), flush=True)
-    assert (flags == 1).all()
+    assert (flags == 3).all()
 
 
 def test_two_streams_get_separate_automatic_workspaces():
