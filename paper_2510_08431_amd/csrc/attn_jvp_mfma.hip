@@ -366,6 +366,15 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         if constexpr (part == 0) {
             sp0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
             sp1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
+            if constexpr (ONLINE) {
+                // Online tier: everything downstream (l, H~, r) is formed from the weights AS ROUNDED to fp16, so
+                // that the result is the exact JVP of a softmax whose probabilities are off by 2^-12 relative.
+                // With unrounded weights in l, r and H~ but rounded ones in the O product, B - (r/l) O would keep
+                // the difference times r/l, which is not small on rows whose centre has drifted.
+                const f32x2 w = __builtin_convertvector(__builtin_bit_cast(f16x2, pack_f16(sp0, sp1)), f32x2);
+                sp0 = w[0];
+                sp1 = w[1];
+            }
         } else if constexpr (part == 1) {
             if constexpr (!PRIMAL) {
                 sh0 = sp0 * fmaf(tsv[e], scale_h, -ctr_h);

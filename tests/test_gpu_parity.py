@@ -265,6 +265,74 @@ def test_f16_path_abandons_tiles_that_overflow():
     assert (flags == 3).all()
 
 
+# the online fp16 tier (reference follows the running row maximum, H~ as hi + lo fp16 terms): reached with the
+# fp16 path forced on inputs whose scores are too spread out for a sampled reference (logit std ~8)
+
+@pytest.mark.parametrize("tangents", ["all", "null-kv", "none"])
+@pytest.mark.parametrize("Lq,Lkv", [(32, 64), (128, 65), (200, 333), (129, 127), (31, 1000), (384, 640), (260, 4100)])
+def test_online_fp16_tier_shapes(Lq, Lkv, tangents):
+    """Every tile must be finished by the online fp16 launch (flag 3), on ragged key tails, ragged query tiles, one
+    to 129 key blocks, with all tangents, with tk = tv = NULL and with no tangents at all."""
+    B, H = 1, 2
+    t = random_inputs(1200 + Lq + Lkv, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0, qk_gain=8 ** 0.5)
+    if tangents != "all":
+        t["tk"].zero_(); t["tv"].zero_()
+    if tangents == "none":
+        t["tq"].zero_()
+    scale = 128 ** -0.5
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    args = [dev["q"], dev["k"], dev["v"]] + {"all": [dev["tq"], dev["tk"], dev["tv"]], "null-kv": [dev["tq"], None, None],
+                                             "none": [None, None, None]}[tangents]
+    o, to, lse = binding.attn_jvp_fwd_ex(*args, scale, kernel=binding.KERNEL_MFMA, flags=binding.FLAG_F16_ALWAYS)
+    torch.cuda.synchronize()
+    flags = f16_tile_flags(B, H, Lq)
+    assert (flags == 3).all(), flags.tolist()
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    label = f"online fp16 tier, tangents={tangents} Lq={Lq} Lkv={Lkv}"
+    if tangents == "none":
+        assert to is None
+        e_o = rel_err(o.cpu().double().numpy(), ref[0])
+        e_lse = float(np.abs(lse.cpu().double().numpy() - ref[2]).max())
+        print(f"[{label}] err O={e_o:.3e} lse={e_lse:.3e}", flush=True)
+        assert e_o <= TOL[torch.bfloat16][0] and e_lse <= TOL[torch.bfloat16][2]
+        return
+    compare((o.cpu().double().numpy(), to.cpu().double().numpy(), lse.cpu().double().numpy()), ref, torch.bfloat16, label)
+
+
+def test_online_fp16_tier_moving_reference():
+    """Keys ordered so that every query's scores climb by ~0.7 binades per key along the sequence: the reference
+    and the tangent-score centre move in nearly every block, and the accumulators are rescaled each time."""
+    B, H, Lq, Lkv, d = 1, 1, 256, 2560, 128
+    g = torch.Generator().manual_seed(77)
+    u = torch.randn(d, generator=g)
+    u /= u.norm()
+    t = random_inputs(1300, B, H, Lq, Lkv, d, torch.bfloat16, tangent_std=1.0)
+    t["q"] = (0.5 * t["q"].float() + 4.0 * u).to(torch.bfloat16)
+    t["k"] = (t["k"].float() + torch.arange(Lkv).view(1, 1, Lkv, 1) * 1.4 * u).to(torch.bfloat16)
+    scale = d ** -0.5
+    got = run_gpu(t, scale, binding.KERNEL_MFMA, binding.FLAG_F16_ALWAYS)
+    flags = f16_tile_flags(B, H, Lq)
+    assert (flags == 3).all(), flags.tolist()
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    compare(got, ref, torch.bfloat16, "online fp16 tier, climbing scores")
+
+
+def test_online_fp16_tier_blhd_layout_gives_the_same_bits():
+    B, H, Lq, Lkv = 2, 2, 200, 333
+    t = random_inputs(1400, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0, qk_gain=8 ** 0.5)
+    scale = 128 ** -0.5
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    a = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                kernel=binding.KERNEL_MFMA, flags=binding.FLAG_F16_ALWAYS)
+    torch.cuda.synchronize()
+    assert (f16_tile_flags(B, H, Lq) == 3).all()
+    tt = {n: x.permute(0, 2, 1, 3).contiguous() for n, x in dev.items()}
+    b = binding.attn_jvp_fwd_ex(tt["q"], tt["k"], tt["v"], tt["tq"], tt["tk"], tt["tv"], scale,
+                                kernel=binding.KERNEL_MFMA, flags=binding.FLAG_F16_ALWAYS, layout=binding.LAYOUT_BLHD)
+    torch.cuda.synchronize()
+    assert torch.equal(b[0].permute(0, 2, 1, 3), a[0]) and torch.equal(b[1].permute(0, 2, 1, 3), a[1]) and torch.equal(b[2], a[2])
+
+
 def test_two_streams_get_separate_automatic_workspaces():
     """Calls that may overlap (two streams) must not share the binding's automatic scratch: each result must be what
     the same call gives alone."""
