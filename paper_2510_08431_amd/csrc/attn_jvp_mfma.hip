@@ -23,10 +23,11 @@
 // b+1 run over block b's softmax arithmetic, the value MFMAs of block b over the fetch of block b+1's
 // scores from the accumulation registers; LDS fragments are requested several MFMAs ahead of their use.
 //
-// Three instantiations differ in how the weights P~ and H~ enter the three value contractions: single bf16
-// terms (MODE_BF16), hi + lo bf16 pairs (MODE_BF16_SPLIT), or single fp16 terms against power-of-two-scaled fp16
-// copies of V and tV that a pre-pass left in the caller's workspace (MODE_F16).  On the fp16 path the host
-// launches MODE_F16 and then MODE_BF16_SPLIT; per-tile flags in the workspace say which of the two finishes a tile.
+// Four instantiations differ in how the weights P~ and H~ enter the three value contractions: single bf16
+// terms (MODE_BF16), hi + lo bf16 pairs (MODE_BF16_SPLIT), or fp16 terms against power-of-two-scaled fp16
+// copies of V and tV that a pre-pass left in the caller's workspace (MODE_F16 with a sampled, fixed exponent
+// reference; MODE_F16_ONLINE with a running one, for peaked rows).  On the fp16 path the host launches MODE_F16,
+// MODE_F16_ONLINE and MODE_BF16_SPLIT in turn; per-tile flags in the workspace say which of them finishes a tile.
 //
 // Numerics: bf16 operands, fp32 accumulation; softmax in base 2 with scale*log2(e) folded into one FMA.
 // The fast sweep fixes the exponent reference m per row after the first block (all of Alg. 2's rescale
@@ -189,7 +190,8 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int
 //   MODE_BF16      one bf16 term each: Alg. 2's 6 matrix products per key block, 8-bit weights;
 //   MODE_BF16_SPLIT hi + lo bf16 pairs: 9 products, ~16-bit weights, no extra memory;
 //   MODE_F16       one fp16 term each against fp16 copies of V, tV (made by the pre-pass, scaled per head by
-//                  powers of two so that nothing over- or underflows): 6 products, 11-bit weights.
+//                  powers of two so that nothing over- or underflows): 6 products, 11-bit weights;
+//   MODE_F16_ONLINE the same copies, P~ as one fp16 term, H~ as hi + lo fp16 terms: 7 products.
 //
 // ZT ("zero key/value tangents", cross-attention onto a context that does not depend on the differentiated
 // variable; template value TAN_QUERY): tK = tV = 0 are not passed at all.  tS = scale tQ K^T and tO = tP V then need 4 of the 6 products, and
