@@ -50,7 +50,7 @@ constexpr int MFMA_TILE_ROWS = 128;   // query rows per workgroup of the MFMA ke
 
 // fp16 value path: bytes of device scratch it needs, and the pre-pass that fills it.  Workspace layout, each part
 // rounded up to 256 bytes: per-head statistics (8 floats per head) | one int per MFMA workgroup (hand-over flags
-// between the fp16 launch and the bf16-pair launch) | scaled fp16 copy of V | scaled fp16 copy of tV.
+// between the launches of the fp16 path: sampled-reference fp16, online fp16, bf16 pairs) | scaled fp16 copy of V | scaled fp16 copy of tV.
 struct F16Workspace {
     float* stats;
     int* wg_flags;
