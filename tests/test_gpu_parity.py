@@ -299,6 +299,24 @@ def test_online_fp16_tier_shapes(Lq, Lkv, tangents):
     compare((o.cpu().double().numpy(), to.cpu().double().numpy(), lse.cpu().double().numpy()), ref, torch.bfloat16, label)
 
 
+@pytest.mark.parametrize("vgain,tgain", [(1e-4, 1e-5), (3e3, 1e4), (1.0, 1e-6), (50.0, 0.0)])
+def test_online_fp16_tier_value_and_tangent_magnitudes(vgain, tgain):
+    """Peaked rows with V and the tangents far from unit scale (per-head power-of-two scaling of the fp16 copies)."""
+    B, H, Lq, Lkv = 1, 2, 200, 700
+    t = random_inputs(78, B, H, Lq, Lkv, 128, torch.bfloat16, qk_gain=8 ** 0.5)
+    t["v"] = (t["v"].float() * vgain).to(torch.bfloat16)
+    for n in ("tq", "tk", "tv"):
+        t[n] = (t[n].float() * tgain).to(torch.bfloat16)
+    t["tv"] = (t["tv"].float() * 7.0).to(torch.bfloat16)
+    got = run_gpu(t, 128 ** -0.5, binding.KERNEL_MFMA, binding.FLAG_F16_ALWAYS)
+    assert (f16_tile_flags(B, H, Lq) == 3).all()
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], 128 ** -0.5)
+    if tgain == 0.0:
+        assert np.all(got[1] == 0.0)
+        got = (got[0], ref[1], got[2])
+    compare(got, ref, torch.bfloat16, f"online fp16 tier, magnitudes v*{vgain} t*{tgain}")
+
+
 def test_online_fp16_tier_moving_reference():
     """Keys ordered so that every query's scores climb by ~0.7 binades per key along the sequence: the reference
     and the tangent-score centre move in nearly every block, and the accumulators are rescaled each time."""
