@@ -209,6 +209,8 @@ def main():
         "config": {"workload": workload, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
                    "variant": args.variant, "kv_tangents": "null" if args.null_kv_tangents else "tensors", "layout": args.layout},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        # counted: 12 Lq Lkv d per head (all six products); with tk = tv = NULL four of the six are executed
+        "tflops_executed": round(tflops * (8.0 / 12.0 if args.null_kv_tangents else 1.0), 2),
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": peak, "unit": "TFLOP/s",
                      "frac": round(kern_tflops / peak, 4), "traffic": traffic,
                      "kernel": kernel_name,
