@@ -213,3 +213,11 @@ def test_image_dit_shape_in_fp32_sampled_rows():
         sl = {n: x[b:b + 1, h:h + 1] for n, x in t.items()}
         ref = oracle(sl, sc(d), rows=rows)
         compare(tuple(x[b:b + 1, h:h + 1] for x in got), ref, f"mfma-f32 image-DiT shape b{b} h{h}", L, rows=rows)
+
+
+def test_video_length_key_sequence():
+    """Lkv = 32760 (the video workloads' length: 1023 full key blocks and a ragged one of 24), two heads, two query
+    tiles, every row compared."""
+    B, H, Lq, Lkv, d = 1, 2, 200, 32760, 128
+    t = random_inputs(3276, B, H, Lq, Lkv, d, tangent_std=0.5)
+    compare(to_np(run(t, sc(d))), oracle(t, sc(d)), "mfma-f32 Lkv=32760", Lkv)
