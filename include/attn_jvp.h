@@ -103,10 +103,12 @@ typedef struct attn_jvp_opts {
                                attn_jvp_workspace_bytes(...) bytes the MFMA kernel runs its fp16 value path: V, tV
                                are first copied there as per-head power-of-two-scaled fp16, and the weights P~, H~
                                enter the value contractions as single fp16 terms (6 matrix products per key block,
-                               11-bit weights).  Query tiles whose scores are too spread out for fp16 weights
-                               (standard deviation of a row's scaled scores above ~3.3) are done with bf16 pairs
-                               by a second launch.  Without a workspace, and for Lkv < 2048: hi + lo bf16 pairs
-                               everywhere (9 products, ~16-bit weights). */
+                               11-bit weights) against an exponent reference sampled before the sweep.  Query
+                               tiles whose scores are too spread out for that (standard deviation of a row's
+                               scaled scores above ~3.3) are done by a second launch with a running reference
+                               and H~ as hi + lo fp16 terms (7 products); there lse carries the fp16 rounding of
+                               the dominant weight (at most 2^-11 absolute).  Without a workspace, and for
+                               Lkv < 2048: hi + lo bf16 pairs everywhere (9 products, ~16-bit weights). */
     size_t workspace_bytes; /* size of `workspace` */
     void*  timing_events[2]; /* optional hipEvent_t pair (created by the caller, with timing enabled), or NULL:
                                [0] is recorded on `stream` immediately before the main attention kernel and [1]
