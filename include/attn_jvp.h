@@ -90,7 +90,8 @@ extern "C" {
 #define ATTN_JVP_FLAG_NO_F16 2    /* MFMA kernel only: do not use the fp16 value path even if a workspace is given */
 #define ATTN_JVP_FLAG_F16_ALWAYS 4 /* MFMA kernel only: use the fp16 value path (given a workspace) for short key
                                      sequences too; without it Lkv < 2048 takes the bf16 pairs, which are faster
-                                     there (the fp16 path's pre-pass and key sampling do not pay off) */
+                                     there (the fp16 path's pre-pass and key sampling do not pay off), and so do
+                                     tiles with widely spread scores below ~10k keys */
 
 typedef struct attn_jvp_opts {
     int    in_dtype;        /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */

@@ -199,7 +199,12 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int
 constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2, MODE_F16_ONLINE = 3;
 // MODE_F16_ONLINE: fp16 weights as MODE_F16, but the exponent reference follows the running row maximum (Alg. 2's
 // rescaling, done lazily) instead of being fixed from a sample: the tier for the tiles MODE_F16 declines or abandons.
-constexpr float ONLINE_SLACK = 4.f;   // binades by which a block's maximum may exceed the running one before m moves
+constexpr float ONLINE_SLACK = 8.f;   // binades by which a block's maximum may exceed the running one before m moves
+// A move costs a wave about 600 instructions (check, new centre, rescale of 128 accumulator registers), and a row of
+// the stress workload moves 3.3 times with 4 binades of slack, 2.0 times with 8: about 100 us per tile.  Below this
+// many key blocks the bf16 pairs (9 products, but 11 us of fixed cost per tile) finish a tile sooner than the
+// sampled-reference kernel's wasted pre-scan plus the online kernel, so declined tiles go straight to them.
+constexpr int ONLINE_MIN_BLOCKS = 320;     // (ATTN_JVP_FLAG_F16_ALWAYS sets this aside)
 constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
 // TAN selects which tangents exist: TAN_ALL (tQ, tK, tV), TAN_QUERY (tQ only: "ZT" below, zero key/value tangents)
@@ -212,7 +217,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     void* __restrict__ O, void* __restrict__ tO, float* __restrict__ LSE,
     int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
-    int H, int blhd, int out_bf16, int d_out, int out_blhd) {
+    int H, int blhd, int out_bf16, int d_out, int out_blhd, int online_min_blocks) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16 || MODE == MODE_F16_ONLINE;   // fp16 weights and value operands
     constexpr bool PRESCAN = MODE == MODE_F16;                          // fixed reference from a key sample
@@ -499,9 +504,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     //   fp16 weights: H~ (up to 2^8 P~ after scaling) must stay below 2^16 and the weights that carry the sum
     //   (some 5 binades below the largest) above 2^-14, so m has to be close to the true maximum:
     //   m = maximum over a sample of ~16 evenly spaced key blocks (first and last included) + 6 binades.
-    //   fp16 weights, online: m = running maximum - 3 binades, moved (with a rescale of everything accumulated)
-    //   when a block's maximum exceeds the running one by more than ONLINE_SLACK: weights stay below 2^7.
-    constexpr float REF_HEADROOM = PRESCAN ? 6.f : ONLINE ? -3.f : 40.f;
+    //   fp16 weights, online: m = running maximum + 1 binade, moved (with a rescale of everything accumulated)
+    //   when a block's maximum exceeds the running one by more than ONLINE_SLACK: weights stay below 2^7, and
+    //   keys more than 23 binades (16 nats) below the running maximum drop out of the fp16 range.
+    constexpr float REF_HEADROOM = PRESCAN ? 6.f : ONLINE ? 1.f : 40.f;
     constexpr float F16_MAX_GAP = 13.f;
     float headroom = REF_HEADROOM;
     float m_scan = -INFINITY;
@@ -580,7 +586,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         const bool decline = *flag != 0;
         __syncthreads();
         if (decline) {                       // uniform over the workgroup; nothing is in flight
-            if (threadIdx.x == 0) wg_flags[blockIdx.x] = 1;
+            if (threadIdx.x == 0) wg_flags[blockIdx.x] = n_blocks >= online_min_blocks ? 1 : 2;
             return;
         }
         start_rings();
@@ -900,7 +906,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         __syncthreads();
         if constexpr (F16) {
             // the fp16 kernels do not repair: they hand the tile to the launch that follows (online fp16, then bf16 pairs)
-            if (threadIdx.x == 0) wg_flags[blockIdx.x] = redo ? (ONLINE ? 2 : 1) : (ONLINE ? 3 : 0);
+            if (threadIdx.x == 0)
+                wg_flags[blockIdx.x] = redo ? (ONLINE || n_blocks < online_min_blocks ? 2 : 1) : (ONLINE ? 3 : 0);
             if (redo) return;
         } else if (__builtin_expect(redo, 0)) {
             // ============================ safe sweep (rare) ============================
@@ -1030,7 +1037,7 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
                            p.o, p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout, p.out_dtype,
-                           p.d_out, p.out_layout);
+                           p.d_out, p.out_layout, (p.flags & 4) ? 0 : ONLINE_MIN_BLOCKS);   // F16_ALWAYS: never the pairs first
         return hipGetLastError();
     };
     // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence

@@ -238,31 +238,43 @@ def f16_tile_flags(B, H, Lq):
     return flags.reshape(B * H, -1)
 
 
-def test_f16_path_routes_tiles_by_score_spread():
+@pytest.mark.parametrize("flags,second", [(0, 2), (binding.FLAG_F16_ALWAYS, 3)])
+def test_f16_path_routes_tiles_by_score_spread(flags, second):
     """Head 0 has N(0,1) logits (a sampled, fixed reference is fine), head 1 logits of std ~8 (sampled maximum
-    unreliable): the first fp16 launch must keep the first and hand the second to the online fp16 launch; both
-    within tolerance."""
+    unreliable): the first fp16 launch must keep the first and hand the second on: at 4096 keys to the bf16 pairs
+    (flag 2; the online fp16 tier pays off from ~10k keys), to the online fp16 launch (flag 3) when the caller
+    insists on the fp16 path; all within tolerance."""
     B, H, Lq, Lkv = 1, 2, 384, 4096
     t = random_inputs(51, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
     t["q"][:, 1] *= 8 ** 0.5
     t["k"][:, 1] *= 8 ** 0.5
-    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "mixed heads, f16 path")
-    flags = f16_tile_flags(B, H, Lq)
-    print("[tile flags]", flags.tolist(), flush=True)
-    assert (flags[0] == 0).all() and (flags[1] == 3).all()
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "mixed heads, f16 path", flags=flags)
+    tile_flags = f16_tile_flags(B, H, Lq)
+    print("[tile flags]", tile_flags.tolist(), flush=True)
+    assert (tile_flags[0] == 0).all() and (tile_flags[1] == second).all()
 
 
-def test_f16_path_abandons_tiles_that_overflow():
+def test_f16_path_routes_long_peaked_tiles_to_the_online_tier():
+    """Default flags, 12288 keys (384 key blocks): declined tiles go to the online fp16 launch."""
+    B, H, Lq, Lkv = 1, 1, 256, 12288
+    t = random_inputs(53, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0, qk_gain=8 ** 0.5)
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "peaked, 12288 keys, default flags")
+    assert (f16_tile_flags(B, H, Lq) == 3).all()
+
+
+@pytest.mark.parametrize("flags,second", [(0, 2), (binding.FLAG_F16_ALWAYS, 3)])
+def test_f16_path_abandons_tiles_that_overflow(flags, second):
     """One key outside the sampled blocks (key 33; the sample takes every 8th block of 128) scores far above the
     sampled maximum for about half of the queries: the sample statistics look harmless, the fp16 weights
-    overflow, the end-of-sweep check must notice and the online fp16 launch must redo those tiles."""
+    overflow, the end-of-sweep check must notice and a later launch must redo those tiles (bf16 pairs at this
+    length, the online fp16 tier when the caller insists on the fp16 path)."""
     B, H, Lq, Lkv = 1, 1, 512, 4096
     t = random_inputs(52, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
     t["k"][:, :, 33] *= 24.0
-    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "outlier key missed by the sample, f16 path")
-    flags = f16_tile_flags(B, H, Lq)
-    print("[tile flags]", flags.tolist(), flush=True)
-    assert (flags == 3).all()
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "outlier key missed by the sample, f16 path", flags=flags)
+    tile_flags = f16_tile_flags(B, H, Lq)
+    print("[tile flags]", tile_flags.tolist(), flush=True)
+    assert (tile_flags == second).all()
 
 
 # the online fp16 tier (reference follows the running row maximum, H~ as hi + lo fp16 terms): reached with the
