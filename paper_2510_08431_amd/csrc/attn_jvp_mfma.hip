@@ -77,7 +77,8 @@ static_assert(PRESCAN_BLOCKS >= 2 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES 
 // copies per key block to get the scores out.  Written as assembly, the MFMA delivers them where they are needed.
 // The compiler does not see inside: it still orders the LDS reads that produce operand `a` (they are register
 // operands of the statement), but it knows nothing of the 11 wait states an 8-pass MFMA needs before the vector ALU
-// may read its result; the loop provides them itself (SCORE_RESULTS_LAND) after the last score product of a block.
+// may read its result; the loop provides them itself (SCORE_RESULTS_LAND and what follows it) after the last score
+// product of a block.
 // Nor does it know that the result registers are busy until then: a result lane nobody reads later would be handed
 // to the next LDS load at once, which the MFMA would then overwrite.  Every lane of s and ts is therefore read
 // through a pinned copy after the wait (the hand-over in phase 2), and the build checks the compiled assembly for
@@ -85,7 +86,10 @@ static_assert(PRESCAN_BLOCKS >= 2 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES 
 // `b` (a Q or tQ fragment) lives in accumulation registers.  SMFMA0 starts a chain (C = 0), SMFMA continues it.
 #define SMFMA0(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b))
 #define SMFMA(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b))
-#define SCORE_RESULTS_LAND() asm volatile("s_nop 7\n\ts_nop 3" ::: "memory")     // 12 wait states
+// 5 wait states of its own; the other 6 or more of the 11 are the instructions that follow in every instantiation
+// (LDS reads, the wait for the copies, the barrier, the first value MFMA) before the first hand-over copy: the
+// build's check of the compiled assembly counts them, so a schedule that came out shorter would fail the build.
+#define SCORE_RESULTS_LAND() asm volatile("s_nop 4" ::: "memory")
 // value contractions: bf16 or fp16 operands (the fragments are carried as raw 128-bit registers)
 #define VMFMA(a, b, c)                                                                                          \
     (F16 ? __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0) \
