@@ -91,7 +91,7 @@ extern "C" {
 #define ATTN_JVP_FLAG_F16_ALWAYS 4 /* MFMA kernel only: use the fp16 value path (given a workspace) for short key
                                      sequences too; without it Lkv < 2048 takes the bf16 pairs, which are faster
                                      there (the fp16 path's pre-pass and key sampling do not pay off), and so do
-                                     tiles with widely spread scores below ~10k keys */
+                                     tiles with widely spread scores below ~5k keys */
 
 typedef struct attn_jvp_opts {
     int    in_dtype;        /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
@@ -106,9 +106,10 @@ typedef struct attn_jvp_opts {
                                enter the value contractions as single fp16 terms (6 matrix products per key block,
                                11-bit weights) against an exponent reference sampled before the sweep.  Query
                                tiles whose scores are too spread out for that (standard deviation of a row's
-                               scaled scores above ~3.3) are done by a second launch with a running reference
-                               and H~ as hi + lo fp16 terms (7 products); there lse carries the fp16 rounding of
-                               the dominant weight (at most 2^-11 absolute).  Without a workspace, and for
+                               scaled scores above ~3.3) are done by a second launch with a running reference.
+                               On this path the row sums are taken over the weights as rounded, so o, to are
+                               the exact result for probabilities and tangent scores off by 2^-11 relative, and
+                               lse carries the rounding of l (at most 2^-11 absolute).  Without a workspace, and for
                                Lkv < 2048: hi + lo bf16 pairs everywhere (9 products, ~16-bit weights). */
     size_t workspace_bytes; /* size of `workspace` */
     void*  timing_events[2]; /* optional hipEvent_t pair (created by the caller, with timing enabled), or NULL:

@@ -129,6 +129,29 @@ __device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
     const f32x2 v = {lo, hi};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, f16x2));
 }
+// fp32 a * b + c with a taken from one half of a packed fp16 pair (a mixed-precision fused multiply-add: the
+// conversion rides along, so reading the weights back AS ROUNDED costs no instruction of its own).  `b` is a
+// wave-uniform fp32 value in a scalar register for the *_s forms.
+__device__ __forceinline__ float mix_lo(uint32_t h2, float b, float c) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h2), "v"(b), "v"(c));
+    return d;
+}
+__device__ __forceinline__ float mix_hi(uint32_t h2, float b, float c) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h2), "v"(b), "v"(c));
+    return d;
+}
+__device__ __forceinline__ float mix_lo_s(uint32_t h2, float b, float c) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h2), "s"(b), "v"(c));
+    return d;
+}
+__device__ __forceinline__ float mix_hi_s(uint32_t h2, float b, float c) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h2), "s"(b), "v"(c));
+    return d;
+}
 __device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     u32x4 u = {a, b, c, d};
     return __builtin_bit_cast(bf16x8, u);
@@ -195,7 +218,10 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int
 //   MODE_BF16_SPLIT hi + lo bf16 pairs: 9 products, ~16-bit weights, no extra memory;
 //   MODE_F16       one fp16 term each against fp16 copies of V, tV (made by the pre-pass, scaled per head by
 //                  powers of two so that nothing over- or underflows): 6 products, 11-bit weights;
-//   MODE_F16_ONLINE the same copies, P~ as one fp16 term, H~ as hi + lo fp16 terms: 7 products.
+//   MODE_F16_ONLINE the same, with a running exponent reference.
+// In both fp16 modes the row sums l and r are taken over the weights as rounded to fp16, so what comes out is the
+// exact JVP of an attention whose probabilities and centred tangent scores are each off by 2^-11 relative; lse
+// carries that rounding of l (at most 2^-11 absolute, far less when many keys share the weight).
 //
 // ZT ("zero key/value tangents", cross-attention onto a context that does not depend on the differentiated
 // variable; template value TAN_QUERY): tK = tV = 0 are not passed at all.  tS = scale tQ K^T and tO = tP V then need 4 of the 6 products, and
@@ -206,9 +232,10 @@ constexpr int MODE_BF16 = 0, MODE_BF16_SPLIT = 1, MODE_F16 = 2, MODE_F16_ONLINE 
 constexpr float ONLINE_SLACK = 8.f;   // binades by which a block's maximum may exceed the running one before m moves
 // A move costs a wave about 600 instructions (check, new centre, rescale of 128 accumulator registers), and a row of
 // the stress workload moves 3.3 times with 4 binades of slack, 2.0 times with 8: about 100 us per tile.  Below this
-// many key blocks the bf16 pairs (9 products, but 11 us of fixed cost per tile) finish a tile sooner than the
-// sampled-reference kernel's wasted pre-scan plus the online kernel, so declined tiles go straight to them.
-constexpr int ONLINE_MIN_BLOCKS = 320;     // (ATTN_JVP_FLAG_F16_ALWAYS sets this aside)
+// many key blocks (5120 keys) the bf16 pairs (9 products, but 11 us of fixed cost per tile) finish a tile as soon as
+// the sampled-reference kernel's wasted pre-scan plus the online kernel, so declined tiles go straight to them
+// (measured, logit std 8, 16 heads: 4096 keys 0.49 ms pairs / 0.52 online, 6144 keys 1.06 / 0.96, 8192 1.86 / 1.64).
+constexpr int ONLINE_MIN_BLOCKS = 160;     // (ATTN_JVP_FLAG_F16_ALWAYS sets this aside)
 constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
 // TAN selects which tangents exist: TAN_ALL (tQ, tK, tV), TAN_QUERY (tQ only: "ZT" below, zero key/value tangents)
@@ -229,7 +256,6 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // The online tier gets the peaked rows, where a few keys carry a row and the 11 bits of their H~ survive the
     // B - r O cancellation (measured 1.5e-2 of the 2e-2 allowed on the stress workload): there H~ enters the V
     // product as hi + lo fp16 terms, one product more (7 per key block).
-    constexpr bool HSPLIT = ONLINE && TAN != TAN_NONE;
     constexpr bool ZT = TAN != TAN_ALL;          // no key/value tangents
     constexpr bool PRIMAL = TAN == TAN_NONE;     // no tangents at all
     // Hand-over between the launches of the fp16 path, which follow each other on one stream: the fp16 kernel
@@ -351,6 +377,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
     const float c2 = scale * 1.4426950408889634f;   // scores -> base-2 exponent
     float m;                  // per-row exponent reference, fixed for the fast sweep
+    float l_part2 = 0.f, r_part2 = 0.f;
     float l_part, r_part;     // this lane's share of rowsum(P~) and of gH * rowsum(H~), H~ = P~ o (tS - ctr)
     // fp16 path: the O accumulator holds 2^-eV O~, the A+B accumulator 2^-eA (A+B), H~ is formed times gH = 2^(eV-eA)
     float gO = 1.f, gAB = 1.f, gH = 1.f;
@@ -364,7 +391,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     float ctr_h;              // gH * ctr, ctr = per-row centre subtracted from the scaled tangent scores
 
     uint32_t wp[8], wh[8];                              // P~^T, H~^T as packed bf16 pairs, result-register order
-    uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT || HSPLIT ? 8 : 1];    // their low-order parts
+    uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT ? 8 : 1];    // their low-order parts
 
     float sv[16], tsv[16];    // scores of the block whose softmax comes next, in ordinary registers
 
@@ -372,41 +399,53 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // six vector instructions so that the pipelined sweep can put one part behind each MFMA:
     //   0: P~ = exp2(S c2 - m)   1: H~ = P~ (tS scale - ctr)   2: row sums   3: pack P~ (hi, lo)   4: pack H~ (hi, lo)
     float sp0, sp1, sh0, sh1;
+    float one = 1.f;   // kept in a scalar register as an opaque operand of the mixed multiply-adds
+    asm volatile("" : "+s"(one));
     auto softmax_part = [&](auto J, auto PART) __attribute__((always_inline)) {
         constexpr int j = decltype(J)::value, e = 2 * j, part = decltype(PART)::value;
         if constexpr (part == 0) {
             sp0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
             sp1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
-            if constexpr (ONLINE) {
-                // Online tier: everything downstream (l, H~, r) is formed from the weights AS ROUNDED to fp16, so
-                // that the result is the exact JVP of a softmax whose probabilities are off by 2^-12 relative.
-                // With unrounded weights in l, r and H~ but rounded ones in the O product, B - (r/l) O would keep
-                // the difference times r/l, which is not small on rows whose centre has drifted.
-                const f32x2 w = __builtin_convertvector(__builtin_bit_cast(f16x2, pack_f16(sp0, sp1)), f32x2);
-                sp0 = w[0];
-                sp1 = w[1];
-            }
+            // fp16 weights: everything downstream (l, H~, r) is formed from P~ AS ROUNDED to fp16, and r from H~ as
+            // rounded, so that the result is the exact JVP of a softmax whose probabilities and centred tangent
+            // scores are off by 2^-11 relative.  With unrounded values in l, r and H~ but rounded ones in the
+            // products, B - (r/l) O would keep the rounding of a dominant key's weight times its tangent score,
+            // which is not small on peaked rows.  The mixed-precision multiply-adds read the packed halves
+            // directly, so this costs no instruction.
         } else if constexpr (part == 1) {
+            if constexpr (F16) wp[j] = pack_f16(sp0, sp1);   // behind the scale-and-centre of part 1: the exponentials have landed
             if constexpr (!PRIMAL) {
-                sh0 = sp0 * fmaf(tsv[e], scale_h, -ctr_h);
-                sh1 = sp1 * fmaf(tsv[e + 1], scale_h, -ctr_h);
+                if constexpr (F16) {
+                    sh0 = mix_lo(wp[j], fmaf(tsv[e], scale_h, -ctr_h), 0.f);
+                    sh1 = mix_hi(wp[j], fmaf(tsv[e + 1], scale_h, -ctr_h), 0.f);
+                } else {
+                    sh0 = sp0 * fmaf(tsv[e], scale_h, -ctr_h);
+                    sh1 = sp1 * fmaf(tsv[e + 1], scale_h, -ctr_h);
+                }
             }
         } else if constexpr (part == 2) {
-            l_part += sp0 + sp1;
-            if constexpr (!PRIMAL) r_part += sh0 + sh1;
+            if constexpr (F16) {
+                l_part = mix_lo_s(wp[j], one, l_part);      // two chains: low halves, high halves
+                l_part2 = mix_hi_s(wp[j], one, l_part2);
+            } else {
+                l_part += sp0 + sp1;
+                if constexpr (!PRIMAL) r_part += sh0 + sh1;
+            }
         } else if constexpr (part == 3) {
-            const uint32_t ph = F16 ? pack_f16(sp0, sp1) : pack_bf16(sp0, sp1);
-            wp[j] = ph;
-            if constexpr (SPLIT)   // lo = x - hi (exact in fp32), rounded to bf16
-                wpl[j] = pack_bf16(sp0 - __uint_as_float(ph << 16), sp1 - __uint_as_float(ph & 0xffff0000u));
+            if constexpr (!F16) {
+                const uint32_t ph = pack_bf16(sp0, sp1);
+                wp[j] = ph;
+                if constexpr (SPLIT)   // lo = x - hi (exact in fp32), rounded to bf16
+                    wpl[j] = pack_bf16(sp0 - __uint_as_float(ph << 16), sp1 - __uint_as_float(ph & 0xffff0000u));
+            }
         } else if constexpr (part == 4 && !PRIMAL) {
             const uint32_t hh = F16 ? pack_f16(sh0, sh1) : pack_bf16(sh0, sh1);
             wh[j] = hh;
             if constexpr (SPLIT)
                 whl[j] = pack_bf16(sh0 - __uint_as_float(hh << 16), sh1 - __uint_as_float(hh & 0xffff0000u));
-            if constexpr (HSPLIT) {
-                const f32x2 hi = __builtin_convertvector(__builtin_bit_cast(f16x2, hh), f32x2);
-                whl[j] = pack_f16(sh0 - hi[0], sh1 - hi[1]);
+            if constexpr (F16) {
+                r_part = mix_lo_s(hh, one, r_part);
+                r_part2 = mix_hi_s(hh, one, r_part2);
             }
         }
     };
@@ -484,8 +523,6 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 accO[db] = VMFMA(vf, pb, accO[db]);
                 if constexpr (!ZT) accAB[db] = VMFMA(tvf, pb, accAB[db]);
                 if constexpr (!PRIMAL) accAB[db] = VMFMA(vf, hb8, accAB[db]);
-                if constexpr (HSPLIT)
-                    accAB[db] = VMFMA(vf, as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]), accAB[db]);
                 if constexpr (SPLIT) {
                     const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                     accO[db] = VMFMA(vf, pl8, accO[db]);
@@ -637,8 +674,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 lb += pe;
                 if constexpr (!PRIMAL) rb = fmaf(pe, fmaf(tsv[e], scale_h, -ctr_h), rb);
             }
-            l_part *= alpha;
-            r_part *= alpha;
+            l_part = (l_part + l_part2) * alpha; l_part2 = 0.f;
+            r_part = (r_part + r_part2) * alpha; r_part2 = 0.f;
             const float l_row = xhalf_sum(l_part + lb);
             const float r_row = xhalf_sum(r_part + rb);
             const float delta = upd ? r_row / l_row : 0.f;      // gH * (running rowsum(P o tS) minus ctr)
@@ -730,7 +767,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         constexpr int U = decltype(Uc)::value;
         constexpr bool FULL = decltype(FULLc)::value;
         constexpr int PRODUCTS = PRIMAL ? 1 : ZT ? 2 : 3;         // matrix products per score step / per weight term
-        constexpr int GROUP_MFMAS = SPLIT ? 2 * PRODUCTS : HSPLIT ? PRODUCTS + 1 : PRODUCTS;
+        constexpr int GROUP_MFMAS = SPLIT ? 2 * PRODUCTS : PRODUCTS;
         using NS_P1 = std::integral_constant<int, 2 * PRODUCTS>;  // phase 1: two score steps per pair
         using NS_P2 = std::integral_constant<int, GROUP_MFMAS>;   // phase 2: one value group per pair
         using K1 = std::integral_constant<int, (U + 1) & 3>;    // K stage of block b+1
@@ -818,12 +855,6 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 accAB[db] = VMFMA(vfr[gi % VRING], hb8, accAB[db]);
                 behind(std::integral_constant<int, PRODUCTS - 1>{});
             }
-            if constexpr (HSPLIT) {
-                const bf16x8 hl8 = as_bf16x8(whl[4 * t2], whl[4 * t2 + 1], whl[4 * t2 + 2], whl[4 * t2 + 3]);
-                FENCE();
-                accAB[db] = VMFMA(vfr[gi % VRING], hl8, accAB[db]);
-                behind(std::integral_constant<int, PRODUCTS>{});
-            }
             if constexpr (SPLIT) {
                 const bf16x8 pl8 = as_bf16x8(wpl[4 * t2], wpl[4 * t2 + 1], wpl[4 * t2 + 2], wpl[4 * t2 + 3]);
                 FENCE();
@@ -889,7 +920,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // Did the fixed exponent reference hold?  Row sums beyond 2^60 (or not finite) mean some score exceeded the
     // reference by ~100 binades.  Then the WHOLE workgroup redoes its tile with Alg. 2's running maximum.
     {
-        const float l_chk = xhalf_sum(l_part), r_chk = xhalf_sum(r_part);
+        const float l_chk = xhalf_sum(l_part + l_part2), r_chk = xhalf_sum(r_part + r_part2);
         bool bad = !(l_chk < 0x1p60f) || !(fabsf(r_chk) < 0x1p100f);
         if constexpr (F16) {   // an fp16 weight that overflowed (inf) leaves inf or NaN in an accumulator
             float tot = 0.f;
@@ -921,7 +952,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             for (int db = 0; db < 4; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
-            m = -INFINITY; l_part = 0.f; r_part = 0.f; ctr_h = 0.f; headroom = 0.f;
+            m = -INFINITY; l_part = 0.f; r_part = 0.f; l_part2 = 0.f; r_part2 = 0.f; ctr_h = 0.f; headroom = 0.f;
             copy_k(0); copy_v(0);
             for (int b = 0; b < n_blocks; ++b) {
                 const uint32_t off = (uint32_t)(b & 3) * KV_STAGE_BYTES;
@@ -941,8 +972,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                     lb += pe;
                     rb = fmaf(pe, fmaf(tsv[e], scale_h, -ctr_h), rb);
                 }
-                l_part *= alpha;
-                r_part *= alpha;
+                l_part = (l_part + l_part2) * alpha; l_part2 = 0.f;
+                r_part = (r_part + r_part2) * alpha; r_part2 = 0.f;
                 const float l_row = xhalf_sum(l_part + lb);
                 const float r_row = xhalf_sum(r_part + rb);
                 const float delta = r_row / l_row;          // gH * (running rowsum(P o tS) minus ctr)
@@ -965,8 +996,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
     // ---- epilogue: O = O~/l, lse = m + log l, tO = (A + B - (r/l) O~) / l  (r and B both relative to ctr).
     // With accO = O~/gO, accAB = (A+B)/gAB and r_part summing gH H~ (gH = gO/gAB) this is gAB (accAB - mu accO) / l.
-    const float l_row = xhalf_sum(l_part);
-    const float r_row = xhalf_sum(r_part);
+    const float l_row = xhalf_sum(l_part + l_part2);
+    const float r_row = xhalf_sum(r_part + r_part2);
     const float inv_l = 1.f / l_row;
     const float mu = r_row * inv_l;
     const float fo = gO * inv_l, ft = gAB * inv_l;

@@ -242,7 +242,7 @@ def f16_tile_flags(B, H, Lq):
 def test_f16_path_routes_tiles_by_score_spread(flags, second):
     """Head 0 has N(0,1) logits (a sampled, fixed reference is fine), head 1 logits of std ~8 (sampled maximum
     unreliable): the first fp16 launch must keep the first and hand the second on: at 4096 keys to the bf16 pairs
-    (flag 2; the online fp16 tier pays off from ~10k keys), to the online fp16 launch (flag 3) when the caller
+    (flag 2; the online fp16 tier pays off from ~5k keys), to the online fp16 launch (flag 3) when the caller
     insists on the fp16 path; all within tolerance."""
     B, H, Lq, Lkv = 1, 2, 384, 4096
     t = random_inputs(51, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0)
