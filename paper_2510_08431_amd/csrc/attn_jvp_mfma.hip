@@ -253,9 +253,6 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     constexpr bool F16 = MODE == MODE_F16 || MODE == MODE_F16_ONLINE;   // fp16 weights and value operands
     constexpr bool PRESCAN = MODE == MODE_F16;                          // fixed reference from a key sample
     constexpr bool ONLINE = MODE == MODE_F16_ONLINE;                    // reference follows the running maximum
-    // The online tier gets the peaked rows, where a few keys carry a row and the 11 bits of their H~ survive the
-    // B - r O cancellation (measured 1.5e-2 of the 2e-2 allowed on the stress workload): there H~ enters the V
-    // product as hi + lo fp16 terms, one product more (7 per key block).
     constexpr bool ZT = TAN != TAN_ALL;          // no key/value tangents
     constexpr bool PRIMAL = TAN == TAN_NONE;     // no tangents at all
     // Hand-over between the launches of the fp16 path, which follow each other on one stream: the fp16 kernel

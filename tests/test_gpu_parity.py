@@ -277,7 +277,7 @@ def test_f16_path_abandons_tiles_that_overflow(flags, second):
     assert (tile_flags == second).all()
 
 
-# the online fp16 tier (reference follows the running row maximum, H~ as hi + lo fp16 terms): reached with the
+# the online fp16 tier (reference follows the running row maximum): reached with the
 # fp16 path forced on inputs whose scores are too spread out for a sampled reference (logit std ~8)
 
 @pytest.mark.parametrize("tangents", ["all", "null-kv", "none"])
