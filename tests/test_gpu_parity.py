@@ -363,6 +363,25 @@ def test_online_fp16_tier_blhd_layout_gives_the_same_bits():
     assert torch.equal(b[0].permute(0, 2, 1, 3), a[0]) and torch.equal(b[1].permute(0, 2, 1, 3), a[1]) and torch.equal(b[2], a[2])
 
 
+@pytest.mark.parametrize("qk_gain,flag", [(1.0, 0), (8 ** 0.5, 3)])
+def test_fp16_kernels_sum_the_rounded_weights(qk_gain, flag):
+    """Cross-attention shape with zero key/value tangents, fp16 path forced: tO = tP V is then the cancellation term
+    B - (r/l) O alone, and the 11-bit rounding of the weights survives in it unless l, H~ are formed from P~ as
+    rounded and r from H~ as rounded (measured on the 512-key workload: 9.4e-3 of RMS(tO) with unrounded sums,
+    1.5e-3 with rounded ones).  Both fp16 kernels (sampled reference on N(0,1) logits, online tier on logit std 8)
+    must stay well inside the 2e-2 tolerance (measured here 2.3e-3 and 3.8e-3); the bound is a third of it."""
+    B, H, Lq, Lkv = 1, 2, 256, 512
+    t = random_inputs(77, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=0.5, qk_gain=qk_gain)
+    t["tk"].zero_()
+    t["tv"].zero_()
+    scale = 128 ** -0.5
+    got = run_gpu_no_kv_tangents(t, scale, binding.KERNEL_MFMA, flags=binding.FLAG_F16_ALWAYS)
+    assert (f16_tile_flags(B, H, Lq) == flag).all()
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    e_o, e_to = compare(got, ref, torch.bfloat16, f"fp16 forced, no tK/tV, gain {qk_gain:.2f}")
+    assert e_to <= 7e-3, e_to
+
+
 def test_two_streams_get_separate_automatic_workspaces():
     """Calls that may overlap (two streams) must not share the binding's automatic scratch: each result must be what
     the same call gives alone."""
