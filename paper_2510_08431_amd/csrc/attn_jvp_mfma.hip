@@ -113,7 +113,9 @@ __device__ __forceinline__ s16x4 lds_read_tr_b64(uint32_t addr) {
 }
 __device__ __forceinline__ float xhalf_max(float x) {   // max of lane l and lane l^32, in both
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    float d;   // as assembly: fmaxf would first canonicalise both halves (two more instructions)
+    asm("v_max_f32 %0, %1, %2" : "=v"(d) : "v"(r[0]), "v"(r[1]));
+    return d;
 }
 __device__ __forceinline__ float xhalf_sum(float x) {
     auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -497,12 +499,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 #pragma unroll
         for (int e = 0; e < 16; ++e) { sv[e] = s[e]; tsv[e] = ts[e]; }
     };
+    // Row maximum of the 16 scores a lane holds, times c2.  Written with the three-operand maximum as assembly: the
+    // compiler's own fmaxf first canonicalises every operand it did not produce itself (one extra v_max per score).
     auto row_max = [&]() __attribute__((always_inline)) -> float {
-        float t0 = fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3]));
-        float t1 = fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7]));
-        float t2_ = fmaxf(fmaxf(sv[8], sv[9]), fmaxf(sv[10], sv[11]));
-        float t3 = fmaxf(fmaxf(sv[12], sv[13]), fmaxf(sv[14], sv[15]));
-        return xhalf_max(fmaxf(fmaxf(t0, t1), fmaxf(t2_, t3))) * c2;
+        auto max3 = [](float a, float b, float c) __attribute__((always_inline)) {
+            float d;
+            asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+            return d;
+        };
+        const float t0 = max3(sv[0], sv[1], sv[2]), t1 = max3(sv[3], sv[4], sv[5]), t2_ = max3(sv[6], sv[7], sv[8]);
+        const float t3 = max3(sv[9], sv[10], sv[11]), t4 = max3(sv[12], sv[13], sv[14]);
+        const float u0 = max3(t0, t1, t2_), u1 = max3(t3, t4, sv[15]);
+        return xhalf_max(max3(u0, u1, u1)) * c2;
     };
     auto plain_values = [&](uint32_t stage_off) __attribute__((always_inline)) {   // unscheduled: safe sweep
 #pragma unroll
@@ -665,9 +673,14 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             const float m_new = upd ? mb + REF_HEADROOM : m;
             const float alpha = __builtin_amdgcn_exp2f(m - m_new);
             float lb = 0.f, rb = 0.f;
+            // (an opaque copy of the new reference: seeing the same expression here and in the softmax that follows,
+            // the compiler would otherwise hoist that softmax's exponentials out of their slots behind the MFMAs
+            // into one block after this branch)
+            float m_cold = m_new;
+            asm volatile("" : "+v"(m_cold));
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m_new));
+                const float pe = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m_cold));
                 lb += pe;
                 if constexpr (!PRIMAL) rb = fmaf(pe, fmaf(tsv[e], scale_h, -ctr_h), rb);
             }
