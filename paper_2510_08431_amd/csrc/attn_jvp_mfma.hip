@@ -66,7 +66,7 @@ constexpr int PRESCAN_BLOCKS = ATTN_JVP_PRESCAN_BLOCKS;   // key blocks sampled 
 constexpr int KV_STAGE_BYTES = 2 * TENSOR_BYTES;        // K|tK or V|tV
 constexpr int V_RING_BASE = NSTAGE * KV_STAGE_BYTES;    // K ring at [0, 64 KiB), V ring at [64 KiB, 128 KiB)
 constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
-static_assert(PRESCAN_BLOCKS >= 2 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES && 2 * PRESCAN_BLOCKS + 16 < 64,
+static_assert(PRESCAN_BLOCKS >= 4 && PRESCAN_BLOCKS % 2 == 0 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES && 2 * PRESCAN_BLOCKS + 16 < 64,
               "the samples share the ring area, and their loads plus the Q fetch must fit the 6-bit vmcnt counter");
 
 // nothing may be scheduled across a fence: the instruction order between fences is the issue order
@@ -315,9 +315,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // fp16 path: the K rows of up to PRESCAN_BLOCKS evenly spaced key blocks (first and last included), sample i at
     // LDS offset i * 8 KiB (the area the rings use later), all requested at once so that one memory latency
     // covers them and the Q fetch
-    const int ns = n_blocks < PRESCAN_BLOCKS ? n_blocks : PRESCAN_BLOCKS;
+    // Half as many below 8192 keys: a row's sample of 256 keys then sits as far below the row's true maximum (in
+    // standard deviations of the scores) as 512 keys do on the long sequences, and each sampled block costs a tile
+    // of a short sequence more (config 2, 4096 keys: 2.3 % of the step).
+    const int max_samples = n_blocks < 256 ? PRESCAN_BLOCKS / 2 : PRESCAN_BLOCKS;
+    const int ns = n_blocks < max_samples ? n_blocks : max_samples;
     auto sample_block = [&](int i) -> int {
-        return n_blocks <= PRESCAN_BLOCKS ? i : (int)(((long)i * (n_blocks - 1)) / (PRESCAN_BLOCKS - 1));
+        return n_blocks <= max_samples ? i : (int)(((long)i * (n_blocks - 1)) / (max_samples - 1));
     };
     if constexpr (PRESCAN) {
         for (int i = 0; i < ns; ++i) {
@@ -549,7 +553,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     //   bf16 weights: m = block-0 maximum + 40 binades; fine while later scores exceed it by < ~100 binades.
     //   fp16 weights: H~ (up to 2^8 P~ after scaling) must stay below 2^16 and the weights that carry the sum
     //   (some 5 binades below the largest) above 2^-14, so m has to be close to the true maximum:
-    //   m = maximum over a sample of ~16 evenly spaced key blocks (first and last included) + 6 binades.
+    //   m = maximum over a sample of 16 evenly spaced key blocks (8 below 8192 keys; first and last included) + 6 binades.
     //   fp16 weights, online: m = running maximum + 1 binade, moved (with a rescale of everything accumulated)
     //   when a block's maximum exceeds the running one by more than ONLINE_SLACK: weights stay below 2^7, and
     //   keys more than 23 binades (16 nats) below the running maximum drop out of the fp16 range.
@@ -611,10 +615,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         // up to ~F16_MAX_GAP binades above the sample's.  For scores with standard deviation sigma the maximum
         // over all keys exceeds the maximum over a few hundred sampled keys by ~1.2 sigma, rarely by more than
         // 2.7 sigma; rows with 2.7 sigma above the limit are left to the bf16-pair kernel, which has the exponent
-        // range for them.  The same rule is applied when the sample covers every block and its maximum is exact:
-        // on such peaked rows the 11-bit weights are also the less accurate choice (the rounding of a dominant
-        // key's H~ survives the B - r O cancellation).  A wrong guess costs time only: the end-of-sweep check
-        // catches overflow.
+        // range for them.  The same rule is applied when the sample covers every block and its maximum is exact,
+        // so that the kernel a row gets does not depend on the length of the key sequence.  A wrong guess costs
+        // time only: the end-of-sweep check catches overflow.
         bool risky = false;
         if (n_stat >= BC) {
             const float inv_n = 1.f / (float)n_stat;
