@@ -93,6 +93,15 @@ extern "C" {
                                      there (the fp16 path's pre-pass and key sampling do not pay off), and so do
                                      tiles with widely spread scores below ~5k keys */
 
+#define ATTN_JVP_FLAG_NO_LOCKSTEP 8 /* MFMA kernel only: on the fp16 path's running-reference tier (key sequences of
+                                     32768 keys or more), do not hold back the start of a query tile until the
+                                     tiles that will share its XCD's L2 have started too (a wait of at most
+                                     100 us per tile).  Results are identical either way; the wait keeps those
+                                     tiles in step on their key/value stream (measured 273 against 329 ms on
+                                     the 75600-key stress workload).  For callers that run other kernels on the
+                                     same GPU at the same time, where an XCD does not hold a full round of
+                                     this kernel's workgroups and every wait would run to its limit. */
+
 typedef struct attn_jvp_opts {
     int    in_dtype;        /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
     int    out_dtype;       /* ATTN_JVP_OUT_FP32 or ATTN_JVP_OUT_INPUT: dtype of o, to */

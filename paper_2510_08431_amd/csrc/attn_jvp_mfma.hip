@@ -238,6 +238,9 @@ constexpr float ONLINE_SLACK = 8.f;   // binades by which a block's maximum may 
 // the sampled-reference kernel's wasted pre-scan plus the online kernel, so declined tiles go straight to them
 // (measured, logit std 8, 16 heads: 4096 keys 0.49 ms pairs / 0.52 online, 6144 keys 1.06 / 0.96, 8192 1.86 / 1.64).
 constexpr int ONLINE_MIN_BLOCKS = 160;     // (ATTN_JVP_FLAG_F16_ALWAYS sets this aside)
+constexpr int LOCKSTEP_MIN_BLOCKS = 1024;            // tiles of at least 1.3 ms: a wasted wait is at most 8 % of one
+constexpr unsigned long long LOCKSTEP_WAIT_TICKS = 10000;   // 100 us of the 100 MHz wall clock
+constexpr int LOCKSTEP_MAX_POLLS = 2048;
 constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
 // TAN selects which tangents exist: TAN_ALL (tQ, tK, tV), TAN_QUERY (tQ only: "ZT" below, zero key/value tangents)
@@ -250,7 +253,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     void* __restrict__ O, void* __restrict__ tO, float* __restrict__ LSE,
     int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
-    int H, int blhd, int out_bf16, int d_out, int out_blhd, int online_min_blocks) {
+    int H, int blhd, int out_bf16, int d_out, int out_blhd, int online_min_blocks, int lockstep_slots) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16 || MODE == MODE_F16_ONLINE;   // fp16 weights and value operands
     constexpr bool PRESCAN = MODE == MODE_F16;                          // fixed reference from a key sample
@@ -263,6 +266,27 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // abandon one itself; the bf16-pair kernel, given the flags, works on exactly the tiles flagged 2.
     if constexpr (ONLINE) {
         if (wg_flags[blockIdx.x] != 1) return;
+        // Lock-step start of the tiles that share an XCD's L2 (lockstep_slots = workgroups an XCD holds at a time, 0 =
+        // off).  The tiles of this tier take different times (moves of the reference), and over many rounds of
+        // tiles the workgroups of an XCD drift apart until each streams K and V from memory on its own.  Each
+        // working workgroup takes a ticket of its XCD and waits until its round of lockstep_slots tickets is
+        // complete, i.e. until the neighbours it will share its key stream with have started too.  The wait is
+        // bounded twice (wall clock and iteration count), so it ends whatever the other workgroups do: the last,
+        // partial round of a launch simply waits out the limit once.
+        if (lockstep_slots > 0) {
+            if (threadIdx.x == 0) {
+                int* ticket = wg_flags + (((int)gridDim.x * 4 + 255) & ~255) / 4 + (blockIdx.x & 7) * 16;
+                const int mine = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const int full = (mine / lockstep_slots + 1) * lockstep_slots;
+                const unsigned long long t0 = wall_clock64();
+                for (int it = 0; it < LOCKSTEP_MAX_POLLS; ++it) {
+                    if (__hip_atomic_load(ticket, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= full) break;
+                    if (wall_clock64() - t0 > LOCKSTEP_WAIT_TICKS) break;
+                    __builtin_amdgcn_s_sleep(32);
+                }
+            }
+            __syncthreads();
+        }
     } else if constexpr (!F16) {
         if (wg_flags != nullptr && wg_flags[blockIdx.x] != 2) return;
     }
@@ -1077,6 +1101,7 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     const int q_tiles = (p.Lq + BR - 1) / BR;
     const long long blocks = (long long)q_tiles * p.B * p.H;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    int lockstep = 0;   // set for the online launch below
     auto launch = [&](auto kern, const void* v, const void* tv, const float* stats, int* wg_flags) -> hipError_t {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
@@ -1085,7 +1110,8 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
                            p.o, p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout, p.out_dtype,
-                           p.d_out, p.out_layout, (p.flags & 4) ? 0 : ONLINE_MIN_BLOCKS);   // F16_ALWAYS: never the pairs first
+                           p.d_out, p.out_layout, (p.flags & 4) ? 0 : ONLINE_MIN_BLOCKS,   // F16_ALWAYS: never the pairs first
+                           lockstep);
         return hipGetLastError();
     };
     // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence
@@ -1098,6 +1124,7 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     if (f16) {
         hipError_t e = launch_f16_prepass(p, &ws);
         if (e != hipSuccess) return e;
+        if ((p.Lkv + BC - 1) / BC < LOCKSTEP_MIN_BLOCKS || (p.flags & 8)) ws.lockstep_slots = 0;
     }
     MainKernelTimer timer(p);
     hipError_t e;
@@ -1109,7 +1136,9 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
         constexpr int T = decltype(tan)::value;
         if (!f16) return launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T>, p.v, tv, nullptr, nullptr);
         hipError_t err = launch(attn_jvp_mfma_kernel<MODE_F16, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
+        lockstep = ws.lockstep_slots;
         if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_F16_ONLINE, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
+        lockstep = 0;
         if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T>, p.v, tv, nullptr, ws.wg_flags);
         return err;
     };

@@ -127,7 +127,7 @@ Layout layout(int B, int H, int Lq, int Lkv, int d) {
     const size_t heads = (size_t)B * H;
     const size_t tiles = heads * (size_t)((Lq + MFMA_TILE_ROWS - 1) / MFMA_TILE_ROWS);
     auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
-    return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)), up(heads * (size_t)Lkv * d * sizeof(__half))};
+    return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)) + 512, up(heads * (size_t)Lkv * d * sizeof(__half))};
 }
 struct PadArgs {
     const __hip_bfloat16* src[6];   // q, k, v, tq, tk, tv (null = absent)
@@ -207,6 +207,16 @@ hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out) {
     __half* tV16 = reinterpret_cast<__half*>(ws + l.stats_bytes + l.flags_bytes + l.vals_bytes);
     const int n_stats = (int)(heads * 8);
     hipLaunchKernelGGL(zero_stats_kernel, dim3((n_stats + 255) / 256), dim3(256), 0, p.stream, stats, n_stats);
+    // tickets of the online tier's lock-step start: 8 XCDs x one counter per 64 bytes, after the flags
+    float* tickets = reinterpret_cast<float*>(ws + l.stats_bytes + l.flags_bytes - 512);
+    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, p.stream, tickets, 128);
+    {
+        int dev = 0, cus = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess) return e;
+        out->lockstep_slots = cus % 8 == 0 ? cus / 8 : 0;   // one workgroup per compute unit, eight XCDs
+    }
     StatsArgs sa;
     const void* xs[6] = {p.v, p.tv, p.q, p.tq, p.k, p.tk};
     for (int i = 0; i < 6; ++i) {

@@ -50,12 +50,14 @@ constexpr int MFMA_TILE_ROWS = 128;   // query rows per workgroup of the MFMA ke
 
 // fp16 value path: bytes of device scratch it needs, and the pre-pass that fills it.  Workspace layout, each part
 // rounded up to 256 bytes: per-head statistics (8 floats per head) | one int per MFMA workgroup (hand-over flags
-// between the launches of the fp16 path: sampled-reference fp16, online fp16, bf16 pairs) | scaled fp16 copy of V | scaled fp16 copy of tV.
+// between the launches of the fp16 path: sampled-reference fp16, online fp16, bf16 pairs) followed by 512 bytes of
+// lock-step tickets (one counter per XCD, 64 bytes apart) | scaled fp16 copy of V | scaled fp16 copy of tV.
 struct F16Workspace {
     float* stats;
     int* wg_flags;
     const void* v16;
     const void* tv16;
+    int lockstep_slots;   // workgroups of the sweep kernel an XCD holds at a time (its tickets follow the flags, zeroed)
 };
 size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 

@@ -382,6 +382,29 @@ def test_fp16_kernels_sum_the_rounded_weights(qk_gain, flag):
     assert e_to <= 7e-3, e_to
 
 
+@pytest.mark.parametrize("Lq", [256, 33792])
+def test_online_fp16_tier_lockstep_start_changes_no_bit(Lq):
+    """From 32768 keys on, a tile of the online tier waits (at most 100 us) until the tiles that share its XCD's L2
+    have started.  With 2 tiles no round of 32 ever fills and every wait runs to its limit; with 264 tiles (33 per
+    XCD) the first round of each XCD fills and the second waits out the limit.  Either way the call must end and
+    give exactly the bits of a call without the wait, within tolerance of the oracle on sampled rows."""
+    B, H, Lkv = 1, 1, 32768
+    t = random_inputs(1500 + Lq, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0, qk_gain=8 ** 0.5)
+    scale = 128 ** -0.5
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    call = lambda flags: binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale,
+                                                 kernel=binding.KERNEL_MFMA, flags=flags)
+    a = call(0)
+    torch.cuda.synchronize()
+    assert (f16_tile_flags(B, H, Lq) == 3).all()
+    b = call(binding.FLAG_NO_LOCKSTEP)
+    torch.cuda.synchronize()
+    assert all(torch.equal(x, y) for x, y in zip(a, b))
+    rows = np.unique(np.random.default_rng(5).integers(0, Lq, 24))
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale, rows=rows)
+    compare(tuple(x.cpu().double().numpy() for x in a), ref, torch.bfloat16, f"online tier, lock-step start, Lq={Lq}", rows=rows)
+
+
 def test_two_streams_get_separate_automatic_workspaces():
     """Calls that may overlap (two streams) must not share the binding's automatic scratch: each result must be what
     the same call gives alone."""

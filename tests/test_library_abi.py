@@ -56,10 +56,11 @@ def test_opts_struct_layout_matches_header(tmp_path):
 def test_workspace_bytes(lib):
     lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
     n = lib.attn_jvp_workspace_bytes(1, 12, 32760, 32760, 128)
-    # two fp16 copies + 12 x 32 B of statistics (rounded up to 256) + one int per 128-row query tile
-    assert n == 2 * 12 * 32760 * 128 * 2 + 512 + 12 * 256 * 4
+    # two fp16 copies + 12 x 32 B of statistics (rounded up to 256) + one int per 128-row query tile + 512 B of
+    # lock-step tickets
+    assert n == 2 * 12 * 32760 * 128 * 2 + 512 + 12 * 256 * 4 + 512
     pad = (2 * 2 * 256 * 128 * 2) + 4 * (2 * 256 * 128 * 2)           # zero-padded q, tq and k, v, tk, tv
-    f16 = 2 * 2 * 256 * 128 * 2 + 256 + 256                           # fp16 copies + statistics + 4 tile flags
+    f16 = 2 * 2 * 256 * 128 * 2 + 256 + 256 + 512                     # fp16 copies + statistics + 4 tile flags + tickets
     assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 64) == pad + f16
     assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 48) == 0      # the MFMA kernel has no use for d = 48
     assert lib.attn_jvp_workspace_bytes(0, 2, 256, 256, 128) == 0
@@ -112,7 +113,7 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.layout = 2                        # unknown layout
     assert _call(lib, opts=o) == 3
-    o = AttnJvpOpts(); o.flags = 8                         # unknown flag bit
+    o = AttnJvpOpts(); o.flags = 16                        # unknown flag bit
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.workspace = 0x10010; o.workspace_bytes = 1 << 20   # workspace not 256-byte aligned
     assert _call(lib, opts=o) == 4
