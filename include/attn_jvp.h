@@ -148,7 +148,7 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v,
 /*
  * Bytes of scratch the MFMA kernel can use for this shape (0 if it has no use for any).  d = 128: the fp16 value
  * path's 2 fp16 copies of [B,H,Lkv,d], 32 bytes of statistics per (batch, head) and 4 bytes per 128-row query tile,
- * each part rounded up to 256 bytes.  d in {32, 64, 96}: in front of that, zero-padded [.,128] bf16 copies of the
+ * each part rounded up to 256 bytes, and 512 bytes of counters.  d in {32, 64, 96}: in front of that, zero-padded [.,128] bf16 copies of the
  * six inputs (without them the MFMA kernel does not take these head dimensions).  Pure host arithmetic.
  */
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
