@@ -344,8 +344,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // of a short sequence more (config 2, 4096 keys: 2.3 % of the step).
     const int max_samples = n_blocks < 256 ? PRESCAN_BLOCKS / 2 : PRESCAN_BLOCKS;
     const int ns = n_blocks < max_samples ? n_blocks : max_samples;
+    // (32-bit, divisors known at compile time: a 64-bit division by a run-time value is a hundred scalar
+    // instructions, and this is evaluated three times per sample)
     auto sample_block = [&](int i) -> int {
-        return n_blocks <= max_samples ? i : (int)(((long)i * (n_blocks - 1)) / (max_samples - 1));
+        if (n_blocks <= max_samples) return i;
+        const unsigned x = (unsigned)i * (unsigned)(n_blocks - 1);      // < 16 * 2^26
+        return (int)(max_samples == PRESCAN_BLOCKS ? x / (unsigned)(PRESCAN_BLOCKS - 1) : x / (unsigned)(PRESCAN_BLOCKS / 2 - 1));
     };
     if constexpr (PRESCAN) {
         for (int i = 0; i < ns; ++i) {
