@@ -254,12 +254,14 @@ def test_f16_path_routes_tiles_by_score_spread(flags, second):
     assert (tile_flags[0] == 0).all() and (tile_flags[1] == second).all()
 
 
-def test_f16_path_routes_long_peaked_tiles_to_the_online_tier():
-    """Default flags, 12288 keys (384 key blocks): declined tiles go to the online fp16 launch."""
-    B, H, Lq, Lkv = 1, 1, 256, 12288
+@pytest.mark.parametrize("Lkv,second", [(5088, 2), (5120, 3), (12288, 3)])
+def test_f16_path_routes_long_peaked_tiles_to_the_online_tier(Lkv, second):
+    """Default flags: declined tiles go to the online fp16 launch from 160 key blocks (5120 keys) on, to the bf16
+    pairs below."""
+    B, H, Lq = 1, 1, 256
     t = random_inputs(53, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0, qk_gain=8 ** 0.5)
-    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "peaked, 12288 keys, default flags")
-    assert (f16_tile_flags(B, H, Lq) == 3).all()
+    check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, f"peaked, {Lkv} keys, default flags")
+    assert (f16_tile_flags(B, H, Lq) == second).all()
 
 
 @pytest.mark.parametrize("flags,second", [(0, 2), (binding.FLAG_F16_ALWAYS, 3)])
