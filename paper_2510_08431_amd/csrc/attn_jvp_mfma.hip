@@ -428,7 +428,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 
     // Softmax arithmetic of one pair of score elements (2j, 2j+1) -> packed weights, cut into five parts of at most
     // six vector instructions so that the pipelined sweep can put one part behind each MFMA:
-    //   0: P~ = exp2(S c2 - m)   1: H~ = P~ (tS scale - ctr)   2: row sums   3: pack P~ (hi, lo)   4: pack H~ (hi, lo)
+    //   bf16 weights: 0: P~ = exp2(S c2 - m)   1: H~ = P~ (tS scale - ctr)   2: row sums   3: pack P~ (hi, lo)
+    //                 4: pack H~ (hi, lo)
+    //   fp16 weights: 0: P~ = exp2(S c2 - m)   1: pack P~, H~ = P~16 (tS scale - ctr)   2: l += P~16   3: -
+    //                 4: pack H~, r += H~16
     float sp0, sp1, sh0, sh1;
     float one = 1.f;   // kept in a scalar register as an opaque operand of the mixed multiply-adds
     asm volatile("" : "+s"(one));
