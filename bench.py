@@ -188,6 +188,25 @@ def main():
     tflops = cfg.flops / (ms_per_step * 1e-3) / 1e12
     kern_tflops = cfg.flops / (kern_avg_ms * 1e-3) / 1e12
 
+    # Outside the timed region: the same workload through attn_jvp_fwd, the plain 15-argument call, which takes no
+    # workspace from the caller and therefore runs the hi + lo bf16-pair kernel.
+    other_entries = {}
+    if not f32 and args.variant == "default" and layout == binding.LAYOUT_BHLD and not args.null_kv_tangents:
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - c0) * 1e3 / reps
+            tf = cfg.flops / (ms * 1e-3) / 1e12
+            return {"ms_per_call": round(ms, 4), "tflops": round(tf, 2), "pct_of_bf16_mfma_peak": round(100 * tf / PEAK_BF16_TFLOPS, 2)}
+        reps = max(2, min(args.steps, 5))
+        with torch.cuda.stream(torch.cuda.default_stream(dev)):
+            other_entries["attn_jvp_fwd"] = dict(timed(lambda: binding.attn_jvp_fwd(
+                t["q"], t["k"], t["v"], t["tq"], tk, tv, cfg.scale, out=(o, to, lse)), reps), workspace="none (bf16 pairs)")
+
     traffic = None
     try:
         with open(args.traffic_json) as f:
@@ -196,6 +215,17 @@ def main():
         pass
 
     peak = PEAK_FP32_TFLOPS if f32 else PEAK_BF16_TFLOPS
+    # what the path computes in (inputs; matrix products; accumulation), by the route the library takes for this call
+    if f32:
+        arithmetic = "f32 (fp32 MFMA, fp32 accumulate)" if d in (32, 64, 96, 128) else "f32 (vector ALU)"
+    elif not (d in (32, 64, 96, 128) and cfg.scale > 0):
+        arithmetic = "bf16 in, f32 vector ALU"
+    elif args.variant == "fast":
+        arithmetic = "bf16 in, bf16 MFMA (single bf16 weights), f32 accumulate"
+    elif args.variant == "bf16-pairs" or Lkv < 2048:
+        arithmetic = "bf16 in, bf16 MFMA (weights as hi+lo bf16 pairs in the value products), f32 accumulate"
+    else:
+        arithmetic = "bf16 in, bf16 score MFMA + fp16 value MFMA (fp16 weights, V and tV as scaled fp16 copies), f32 accumulate"
     if f32:
         kernel_name = "attn_jvp_mfma_f32_kernel" if d in (32, 64, 96, 128) else "attn_jvp_fp32_kernel"
     else:
@@ -205,7 +235,7 @@ def main():
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if f32 else "bf16", "data": "synthetic",
+        "dtype": arithmetic, "data": "synthetic",
         "config": {"workload": workload, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
                    "variant": args.variant, "kv_tangents": "null" if args.null_kv_tangents else "tensors", "layout": args.layout},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
@@ -217,6 +247,9 @@ def main():
                      "kernel_ms_avg": round(kern_avg_ms, 4), "kernel_ms_min": round(float(np.min(kern_ms)), 4),
                      "kernel_ms_median": round(float(np.median(kern_ms)), 4)},
     }
+
+    if other_entries:
+        out["entry_points_without_caller_workspace"] = other_entries
 
     if not args.no_cpu_baseline:
         # the fp64 oracle, as it stands, on a bounded sample of the same workload: a seeded set of query rows

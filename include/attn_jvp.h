@@ -15,9 +15,10 @@
  * multiplies both S and tS.
  *
  * Memory: every pointer is a DEVICE pointer owned by the caller; the library allocates
- * nothing and keeps no state between calls.  It needs no workspace; if the caller lends one
- * (attn_jvp_opts.workspace, see attn_jvp_workspace_bytes) the bf16 kernel uses its faster
- * fp16-value path.
+ * nothing.  What it keeps between calls is cached per device at first use: the compute-unit
+ * count and the raised dynamic-LDS limits of its kernels.  They need no workspace; if the
+ * caller lends one (attn_jvp_opts.workspace, see attn_jvp_workspace_bytes) the bf16 kernel
+ * uses its faster fp16-value path (6 instead of 9 matrix products per key block).
  *   q, tq        [B, H, Lq,  d]  contiguous, row-major, d fastest (or [B, Lq, H, d], see attn_jvp_opts.layout)
  *   k, v, tk, tv [B, H, Lkv, d]  same
  *   o, to        [B, H, Lq,  d]  float32 (or the input dtype, see attn_jvp_opts.out_dtype), same layout as q
@@ -32,10 +33,15 @@
  * tq, tk and tv may ALL be NULL: no tangents, the plain attention forward that Alg. 2 extends (2 of the 6 products).
  * o and lse are the same bits as with tangents; `to` is not written and may be NULL.
  *
- * Execution: a call validates its arguments on the host, enqueues the kernel on the given
+ * Execution: a call validates its arguments on the host, enqueues its kernels on the given
  * HIP stream and returns without synchronising.  A return value of 0 means "enqueued".
- * On any non-zero return nothing was launched and the outputs are untouched.  No exception
- * or abort crosses this boundary.  Results are deterministic (the only atomics are order-independent maxima in the
+ * Codes 1-4 come from the host-side checks: nothing was launched and the outputs are
+ * untouched.  Everything else that can fail without a launch (device query, LDS limits, grid
+ * sizes) is also done before the first enqueue and returns
+ * ATTN_JVP_LAUNCH_FAILED with nothing launched.  Only when the HIP runtime refuses an enqueue
+ * in the middle of a call (the fp16 value path enqueues up to eight kernels) may earlier
+ * kernels of that call already be on the stream; the outputs are then unspecified.  No
+ * exception or abort crosses this boundary.  Results are deterministic (the only atomics are order-independent maxima in the
  * fp16 path's pre-pass).
  */
 #ifndef ATTN_JVP_H_
@@ -53,7 +59,7 @@ extern "C" {
 #define ATTN_JVP_BAD_SHAPE     2  /* B, H, Lq, Lkv or d <= 0, a product overflows, or scale is not finite */
 #define ATTN_JVP_UNSUPPORTED   3  /* head dim / dtype / kernel choice not built */
 #define ATTN_JVP_MISALIGNED    4  /* a pointer is not 16-byte aligned */
-#define ATTN_JVP_LAUNCH_FAILED 5  /* the HIP runtime refused the launch */
+#define ATTN_JVP_LAUNCH_FAILED 5  /* the HIP runtime refused a set-up call or a launch */
 
 /* attn_jvp_opts.in_dtype / out_dtype */
 #define ATTN_JVP_BF16 0
@@ -81,7 +87,9 @@ extern "C" {
                                      and fp32 accumulation throughout (Alg. 2 as printed), no workspace, flags ignored */
 
 /* attn_jvp_opts.flags */
-#define ATTN_JVP_FLAG_FAST 1      /* MFMA kernel only (not with absent tangents): round the weights P~ and H~ = P~ o tS to ONE bf16 term each
+#define ATTN_JVP_FLAG_FAST 1      /* EXPERIMENTAL, outside the accuracy contract (O within 1e-2, tO within 2e-2 of RMS): kept for
+                                     measurements only.
+                                     MFMA kernel only (not with absent tangents): round the weights P~ and H~ = P~ o tS to ONE bf16 term each
                                      (6 matrix products per key tile, as Alg. 2 counts them) instead of the default
                                      hi + lo bf16 pairs in all three value contractions (9 products) or the fp16 value path.  Faster; the
                                      8-bit rounding then shows in the results: max errors up to ~2e-2 of RMS(O) and
@@ -100,7 +108,10 @@ extern "C" {
                                      tiles in step on their key/value stream (measured 273 against 329 ms on
                                      the 75600-key stress workload).  For callers that run other kernels on the
                                      same GPU at the same time, where an XCD does not hold a full round of
-                                     this kernel's workgroups and every wait would run to its limit. */
+                                     this kernel's workgroups and every wait would run to its limit.
+                                     Hardware assumption behind the wait and behind the kernel's tile map, which
+                                     nothing checks at run time: workgroup w of a launch runs on XCD w mod 8, and
+                                     the GPU is otherwise idle.  If it does not hold, only speed is lost. */
 
 typedef struct attn_jvp_opts {
     int    in_dtype;        /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
@@ -132,6 +143,10 @@ typedef struct attn_jvp_opts {
 /*
  * Alg. 2 with bf16 inputs, float32 o/to/lse, on the default stream, kernel chosen automatically.
  * Returns ATTN_JVP_OK or an error code above.
+ * This call passes no workspace, so at d = 128 it runs the hi + lo bf16-pair kernel: 9 matrix products per key
+ * block where the fp16 value path runs 6, i.e. about 1.35x the time on long key sequences (measured on the
+ * 32760-token self-attention shape, B = 1, H = 12: 20.5-21.3 ms against 15.2-16.4 ms; 37-38 % against 48-52 % of the
+ * bf16 matrix peak).  Callers that want the faster path lend a workspace through attn_jvp_fwd_ex.
  */
 int attn_jvp_fwd(const void* q, const void* k, const void* v,
                  const void* tq, const void* tk, const void* tv,

@@ -167,6 +167,7 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     opts.kernel = int(kernel)
     opts.flags = int(flags)
     opts.layout = int(layout)
+    entry = lib.attn_jvp_fwd_ex
     if isinstance(workspace, str) and workspace == "auto":
         need = lib.attn_jvp_workspace_bytes(B, H, Lq, Lkv, d) if q.dtype == torch.bfloat16 else 0
         workspace = _workspace(q.device, stream, need) if need else None
@@ -179,9 +180,8 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
                 ev.record(stream)
             opts.timing_events[i] = ev.cuda_event
     with torch.cuda.device(q.device):
-        rc = lib.attn_jvp_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(tq), _ptr(tk), _ptr(tv),
-                                 o.data_ptr(), _ptr(to), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale),
-                                 ctypes.byref(opts))
+        rc = entry(q.data_ptr(), k.data_ptr(), v.data_ptr(), _ptr(tq), _ptr(tk), _ptr(tv),
+                   o.data_ptr(), _ptr(to), lse.data_ptr(), B, H, Lq, Lkv, d, float(scale), ctypes.byref(opts))
     if rc != 0:
         raise AttnJvpError(rc, attn_jvp_strerror(rc))
     return o, to, lse

@@ -1,10 +1,48 @@
-// C-ABI entry points: argument validation, kernel choice, launch.  No allocation, no state.
+// C-ABI entry points: argument validation, kernel choice, launch.  No allocation; the only state is what is cached
+// per device at first use (compute-unit count, raised LDS limits).
 #include "../../include/attn_jvp.h"
 #include "launchers.h"
 #include <cmath>
 #include <cstdint>
+#include <mutex>
+#include <set>
+#include <utility>
 
 using attn_jvp::Problem;
+
+namespace attn_jvp {
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_setup_mutex;
+int g_cus[MAX_DEVICES];                         // 0 = not queried yet
+std::set<std::pair<const void*, int>> g_lds_set;   // (kernel, device) pairs whose dynamic-LDS limit has been raised
+}  // namespace
+
+hipError_t device_cus(int* dev, int* cus) {
+    hipError_t e = hipGetDevice(dev);
+    if (e != hipSuccess) return e;
+    if (*dev < 0 || *dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (g_cus[*dev] == 0) {
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, *dev);
+        if (e != hipSuccess) return e;
+        if (n <= 0) return hipErrorInvalidDevice;
+        g_cus[*dev] = n;
+    }
+    *cus = g_cus[*dev];
+    return hipSuccess;
+}
+
+hipError_t ensure_dynamic_lds(const void* kern, int bytes, int dev) {
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (g_lds_set.count({kern, dev})) return hipSuccess;
+    const hipError_t e = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) g_lds_set.insert({kern, dev});
+    return e;
+}
+
+}  // namespace attn_jvp
 
 namespace {
 
@@ -37,9 +75,12 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     for (const void* p : ptrs)
         if (!aligned16(p)) return ATTN_JVP_MISALIGNED;
 
+    void* workspace = opts->workspace;
+    size_t workspace_bytes = opts->workspace ? opts->workspace_bytes : 0;
+
     Problem p{q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale,
               opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags,
-              opts->workspace, opts->workspace ? opts->workspace_bytes : 0,
+              workspace, workspace_bytes,
               static_cast<hipEvent_t>(opts->timing_events[0]), static_cast<hipEvent_t>(opts->timing_events[1]),
               opts->layout, d, opts->layout};
 
@@ -105,11 +146,11 @@ const char* attn_jvp_strerror(int code) {
         case ATTN_JVP_BAD_SHAPE: return "a dimension is not positive, the shape is too large, or scale is not finite";
         case ATTN_JVP_UNSUPPORTED: return "unsupported head dim, dtype, kernel choice or option";
         case ATTN_JVP_MISALIGNED: return "a pointer is not 16-byte aligned";
-        case ATTN_JVP_LAUNCH_FAILED: return "the HIP runtime refused the kernel launch";
+        case ATTN_JVP_LAUNCH_FAILED: return "the HIP runtime refused a set-up call or the kernel launch";
         default: return "unknown attn_jvp error code";
     }
 }
 
-int attn_jvp_version(void) { return 100; }  // 0.1.0
+int attn_jvp_version(void) { return 200; }  // 0.2.0
 
 }  // extern "C"

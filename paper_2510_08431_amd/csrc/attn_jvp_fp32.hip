@@ -179,8 +179,9 @@ hipError_t launch_one(const Problem& p) {
     dim3 grid((p.Lq + BR - 1) / BR, p.B * p.H);
     size_t smem = 4ull * BC * D * sizeof(float);
     auto kern = attn_jvp_fp32_kernel<TIn, TOut, D>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    int dev = 0, cus = 0;
+    hipError_t e = device_cus(&dev, &cus);
+    if (e == hipSuccess) e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (int)smem, dev);
     if (e != hipSuccess) return e;
     MainKernelTimer timer(p);
     hipLaunchKernelGGL(kern, grid, dim3(NTHREADS), smem, p.stream,

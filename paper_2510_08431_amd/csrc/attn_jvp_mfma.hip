@@ -582,14 +582,16 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // that exp2(S c2 - m) stayed representable (see the check below).  ctr is fixed to block 0's value of
     // rowsum(P o tS).  The loop body is straight-line code.
     //   bf16 weights: m = block-0 maximum + 40 binades; fine while later scores exceed it by < ~100 binades.
-    //   fp16 weights: H~ (up to 2^8 P~ after scaling) must stay below 2^16 and the weights that carry the sum
-    //   (some 5 binades below the largest) above 2^-14, so m has to be close to the true maximum:
-    //   m = maximum over a sample of 16 evenly spaced key blocks (8 below 8192 keys; first and last included) + 6 binades.
+    //   fp16 weights: H~ (up to 2^8 P~ after scaling) must stay below 2^16, so P~ below 2^7, and the keys that carry
+    //   the sum must stay inside the fp16 range below that (weights under 2^-25 round to zero), so m has to be close
+    //   to the true maximum: m = maximum over a sample of 16 evenly spaced key blocks (8 below 8192 keys; first and
+    //   last included) + (2.7 sigma - 6) binades, sigma = the row's sampled score spread: the true maximum, which
+    //   rarely exceeds the sampled one by more than 2.7 sigma, then gets a weight of at most 2^6.
     //   fp16 weights, online: m = running maximum + 1 binade, moved (with a rescale of everything accumulated)
     //   when a block's maximum exceeds the running one by more than ONLINE_SLACK: weights stay below 2^7, and
     //   keys more than 23 binades (16 nats) below the running maximum drop out of the fp16 range.
     constexpr float REF_HEADROOM = PRESCAN ? 6.f : ONLINE ? 1.f : 40.f;
-    constexpr float F16_MAX_GAP = 13.f;
+    constexpr float F16_MAX_GAP = 10.f;
     float headroom = REF_HEADROOM;
     float m_scan = -INFINITY;
     if constexpr (PRESCAN) {
@@ -642,11 +644,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             if (i + 1 < ns) scan_one(x1, sample_block(i + 1));
         }
         m_scan = xhalf_max(m_scan) * c2;
-        // Is the sampled maximum likely to be close enough to the true one?  fp16 weights tolerate a true maximum
-        // up to ~F16_MAX_GAP binades above the sample's.  For scores with standard deviation sigma the maximum
+        // Is a fixed reference good enough for this row?  For scores with standard deviation sigma the maximum
         // over all keys exceeds the maximum over a few hundred sampled keys by ~1.2 sigma, rarely by more than
-        // 2.7 sigma; rows with 2.7 sigma above the limit are left to the bf16-pair kernel, which has the exponent
-        // range for them.  The same rule is applied when the sample covers every block and its maximum is exact,
+        // 2.7 sigma.  The wider that uncertainty, the higher the reference has to sit and the less of the fp16
+        // range is left below it for the keys that carry the sum (which spread over more binades, too): rows with
+        // 2.7 sigma above F16_MAX_GAP binades (logit standard deviation above ~2.5) are left to the kernel with the
+        // running reference.  The same rule is applied when the sample covers every block and its maximum is exact,
         // so that the kernel a row gets does not depend on the length of the key sequence.  A wrong guess costs
         // time only: the end-of-sweep check catches overflow.
         bool risky = false;
@@ -654,7 +657,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             const float inv_n = 1.f / (float)n_stat;
             const float mean = xhalf_sum(sum1) * inv_n;
             const float var = fmaxf(xhalf_sum(sum2) * inv_n - mean * mean, 0.f);
-            risky = !(2.7f * __builtin_sqrtf(var) * fabsf(c2) <= F16_MAX_GAP);   // NaN counts as risky
+            const float reach = 2.7f * __builtin_sqrtf(var) * fabsf(c2);   // how far above the sampled maximum the true one may sit, in binades
+            risky = !(reach <= F16_MAX_GAP);   // NaN counts as risky
+            // The reference sits as LOW as the row's own spread allows (true maximum at weight 2^7 at most, one binade
+            // kept in hand), not a fixed 6 binades above the sampled maximum: a row whose sample happens to contain
+            // an outlying maximum would otherwise push the keys that carry its sum below the fp16 range.
+            headroom = fminf(fmaxf(reach - 6.f, -6.f), REF_HEADROOM);
         }
         __syncthreads();   // everyone is done with the samples before the ring copies overwrite them
         volatile __attribute__((address_space(3))) int* flag =
@@ -676,7 +684,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         __syncthreads();
         plain_scores(0);
         if (n_blocks == 1) mask_scores(0);
-        m = (PRESCAN ? m_scan : row_max()) + REF_HEADROOM;
+        m = (PRESCAN ? m_scan : row_max()) + headroom;
         float lb = 0.f, rb = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -966,6 +974,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     {
         const float l_chk = xhalf_sum(l_part + l_part2), r_chk = xhalf_sum(r_part + r_part2);
         bool bad = !(l_chk < 0x1p60f) || !(fabsf(r_chk) < 0x1p100f);
+        // Sampled reference: weights below 2^-25 round to zero in fp16, so up to Lkv 2^-25 of weight may be missing
+        // from a row's sums; the row is good when that is at most 2^-10 of its l.  (A reference that sits too high
+        // for a row, e.g. because the sample caught an outlying maximum, shows up here.)
+        if constexpr (PRESCAN) bad = bad || !(l_chk >= (float)Lkv * 0x1p-15f);
         if constexpr (F16) {   // an fp16 weight that overflowed (inf) leaves inf or NaN in an accumulator
             float tot = 0.f;
 #pragma unroll
@@ -1098,8 +1110,33 @@ bool mfma_bf16_supports(const Problem& p) {
     return p.in_dtype == 0 && (p.d == D || padded_head_dim(p)) && p.scale > 0.f && !(zt && (p.flags & 1));
 }
 
+// Dynamic-LDS limit of every instantiation a call may launch, raised once per device and before anything is enqueued.
+static hipError_t prepare_kernels(int dev) {
+    const void* kernels[] = {
+        (const void*)attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL>,
+        (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_NONE>, (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_QUERY>,
+        (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_ALL>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_NONE>, (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_QUERY>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_ALL>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_NONE>, (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_QUERY>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_ALL>};
+    for (const void* k : kernels) {
+        const hipError_t e = ensure_dynamic_lds(k, LDS_BYTES, dev);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_mfma_bf16(const Problem& p_in) {
     if (!mfma_bf16_supports(p_in)) return hipErrorInvalidValue;
+    int dev = 0, cus = 0;
+    {   // everything that can fail without a launch comes first: a failure here leaves nothing enqueued
+        hipError_t e = device_cus(&dev, &cus);
+        if (e == hipSuccess) e = prepare_kernels(dev);
+        if (e != hipSuccess) return e;
+        const long long tiles = (long long)((p_in.Lq + BR - 1) / BR) * p_in.B * p_in.H;
+        if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
+    }
     Problem p = p_in;
     if (p_in.d != D) {      // run on zero-padded copies of the inputs; o, to keep the caller's width and layout
         hipError_t e = launch_pad_inputs(p_in, &p);
@@ -1110,9 +1147,6 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     int lockstep = 0;   // set for the online launch below
     auto launch = [&](auto kern, const void* v, const void* tv, const float* stats, int* wg_flags) -> hipError_t {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, LDS_BYTES);
-        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
@@ -1129,7 +1163,7 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
                      (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0;
     F16Workspace ws{};
     if (f16) {
-        hipError_t e = launch_f16_prepass(p, &ws);
+        hipError_t e = launch_f16_prepass(p, cus, &ws);
         if (e != hipSuccess) return e;
         if ((p.Lkv + BC - 1) / BC < LOCKSTEP_MIN_BLOCKS || (p.flags & 8)) ws.lockstep_slots = 0;
     }

@@ -395,8 +395,9 @@ hipError_t launch_one(const Problem& p) {
     constexpr int NT = TAN == TAN_ALL ? 4 : 2;
     constexpr int smem = 2 * NT * BC * D * (int)sizeof(float);
     auto kern = attn_jvp_mfma_f32_kernel<D, TAN>;
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    int dev = 0, cus = 0;
+    hipError_t e = device_cus(&dev, &cus);
+    if (e == hipSuccess) e = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), smem, dev);
     if (e != hipSuccess) return e;
     MainKernelTimer timer(p);
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), smem, p.stream,

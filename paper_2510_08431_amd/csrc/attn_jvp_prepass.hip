@@ -197,7 +197,7 @@ size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
     return l.stats_bytes + l.flags_bytes + 2 * l.vals_bytes;
 }
 
-hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out) {
+hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out) {
     const size_t heads = (size_t)p.B * p.H;
     const Layout l = layout(p.B, p.H, p.Lq, p.Lkv, p.d);
     char* ws = static_cast<char*>(p.workspace);
@@ -210,13 +210,7 @@ hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out) {
     // tickets of the online tier's lock-step start: 8 XCDs x one counter per 64 bytes, after the flags
     float* tickets = reinterpret_cast<float*>(ws + l.stats_bytes + l.flags_bytes - 512);
     hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, p.stream, tickets, 128);
-    {
-        int dev = 0, cus = 0;
-        hipError_t e = hipGetDevice(&dev);
-        if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        if (e != hipSuccess) return e;
-        out->lockstep_slots = cus % 8 == 0 ? cus / 8 : 0;   // one workgroup per compute unit, eight XCDs
-    }
+    out->lockstep_slots = cus % 8 == 0 ? cus / 8 : 0;   // one workgroup per compute unit, eight XCDs
     StatsArgs sa;
     const void* xs[6] = {p.v, p.tv, p.q, p.tq, p.k, p.tk};
     for (int i = 0; i < 6; ++i) {

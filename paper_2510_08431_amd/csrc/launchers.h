@@ -37,6 +37,13 @@ struct MainKernelTimer {
     }
 };
 
+// Facts about the current device and one-time set-up, cached per device; none of it touches a stream, and every
+// launcher calls it BEFORE its first enqueue, so that a failure here leaves nothing launched.
+//   device_cus: index of the current device and its number of compute units (queried once per device);
+//   ensure_dynamic_lds: raises a kernel's dynamic-LDS limit (hipFuncSetAttribute) once per (kernel, device).
+hipError_t device_cus(int* dev, int* cus);
+hipError_t ensure_dynamic_lds(const void* kern, int bytes, int dev);
+
 // Each returns hipSuccess/hip error of the launch, or hipErrorInvalidValue when the
 // (dtype, d) combination is not built for that kernel.
 hipError_t launch_fp32_vector(const Problem& p);
@@ -67,7 +74,7 @@ size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 constexpr int MFMA_HEAD_DIM = 128;
 size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv);
 hipError_t launch_pad_inputs(const Problem& p, Problem* padded);
-hipError_t launch_f16_prepass(const Problem& p, F16Workspace* out);
+hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out);
 
 // RMS normalisation with gain + JVP over `rows` rows of length d
 struct RmsNormProblem {

@@ -815,3 +815,80 @@ def test_mfma_safe_sweep_fallback():
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, bf16 pairs", flags=binding.FLAG_NO_F16)
     check_full(t, 128 ** -0.5, binding.KERNEL_MFMA, "safe sweep fallback, fast variant", flags=binding.FLAG_FAST,
                tol=FAST_TOL)
+
+
+# ------------------------------------------------------------------ the fp16 path around its own routing boundary, at video length
+
+def _timed_call(dev, scale, flags, reps=2):
+    """One warm-up call, then `reps` timed ones (HIP events on the current stream); returns outputs and ms per call."""
+    args = (dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale)
+    out = binding.attn_jvp_fwd_ex(*args, kernel=binding.KERNEL_MFMA, flags=flags)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(reps):
+        binding.attn_jvp_fwd_ex(*args, kernel=binding.KERNEL_MFMA, flags=flags, out=out)
+    b.record()
+    torch.cuda.synchronize()
+    return tuple(x.cpu().double().numpy() for x in out), a.elapsed_time(b) / reps
+
+
+def _check_both_flag_settings(t, scale, label, B, H, Lq):
+    """Default flags and F16_ALWAYS on the same inputs against the oracle (every row); returns the tile flags of both."""
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    dev = {n: x.to(DEV) for n, x in t.items()}
+    flags_seen = {}
+    for name, fl in (("default", 0), ("f16-always", binding.FLAG_F16_ALWAYS)):
+        got, ms = _timed_call(dev, scale, fl)
+        tile_flags = f16_tile_flags(B, H, Lq)
+        print(f"[{label} {name}] {ms:.3f} ms per call, tile flags {tile_flags.tolist()}", flush=True)
+        compare(got, ref, torch.bfloat16, f"{label} {name}")
+        assert np.isin(tile_flags, (0, 2, 3)).all()          # every tile finished by exactly one launch
+        flags_seen[name] = tile_flags
+    return flags_seen
+
+
+@pytest.mark.parametrize("std", [1.5, 2.0, 2.5, 3.0, 3.25, 3.5, 4.0, 5.0])
+def test_f16_path_across_the_routing_boundary_at_video_length(std):
+    """The sampled-reference fp16 kernel declines a tile when a row's score spread makes a sampled maximum
+    unreliable (standard deviation of the logits above ~2.5, less when one row of the tile is wider than the
+    rest); around that boundary a workload's tiles are split between it and the running-reference fp16 kernel.
+    Logit standard deviations on both sides of it, 32760 keys, every output row against the oracle."""
+    B, H, Lq, Lkv = 1, 2, 384, 32760
+    t = random_inputs(7000 + int(100 * std), B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=1.0, qk_gain=std ** 0.5)
+    seen = _check_both_flag_settings(t, 128 ** -0.5, f"video length, logit std {std}", B, H, Lq)
+    for tile_flags in seen.values():
+        if std <= 1.5:
+            assert (tile_flags == 0).all()       # comfortably inside the sampled-reference kernel's range
+        if std >= 4.0:
+            assert (tile_flags == 3).all()       # comfortably outside: all handed to the running-reference kernel
+
+
+def test_f16_path_heavy_tailed_scores_at_video_length():
+    """Five keys, none of them in a sampled key block nor in the first or last block, score ~20 nats above the rest
+    for every third query: the sample statistics look harmless, the weights of those keys exceed the fp16 range
+    against a sampled reference, the tiles must be abandoned and redone by the running-reference kernel."""
+    B, H, Lq, Lkv, d = 1, 2, 384, 32760, 128
+    t = random_inputs(7101, B, H, Lq, Lkv, d, torch.bfloat16, tangent_std=1.0)
+    g = torch.Generator().manual_seed(7102)
+    u = torch.randn(d, generator=g)
+    u = u / u.norm() * d ** 0.5                               # |u|^2 = d: scale * (a u).(b u) = a b sqrt(d)
+    a = b = (20.0 / d ** 0.5) ** 0.5
+    keys = [1237, 9001, 15555, 22222, 30011]                  # blocks 38, 281, 486, 694, 937 of 1024: not multiples of 1023/15
+    for h in range(H):
+        kf, qf = t["k"][0, h].float(), t["q"][0, h].float()
+        kf[keys] += b * u
+        qf[::3] += a * u
+        t["k"][0, h], t["q"][0, h] = kf.to(torch.bfloat16), qf.to(torch.bfloat16)
+    seen = _check_both_flag_settings(t, d ** -0.5, "video length, heavy-tailed scores", B, H, Lq)
+    assert (seen["default"] == 3).all()                       # every tile holds such queries
+
+
+def test_f16_path_rows_of_different_spread_in_one_tile():
+    """Rows whose logits have standard deviation 1 and 6 alternate inside every 128-row tile."""
+    B, H, Lq, Lkv, d = 1, 2, 384, 32760, 128
+    t = random_inputs(7201, B, H, Lq, Lkv, d, torch.bfloat16, tangent_std=1.0)
+    q = t["q"].float()
+    q[:, :, 1::2] *= 6.0
+    t["q"] = q.to(torch.bfloat16)
+    seen = _check_both_flag_settings(t, d ** -0.5, "video length, rows of std 1 and 6 in one tile", B, H, Lq)
+    assert (seen["default"] == 3).all()

@@ -27,8 +27,8 @@ def declared_functions():
 
 def test_header_symbols_exported(lib):
     names = declared_functions()
-    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_rmsnorm_fwd", "attn_jvp_strerror", "attn_jvp_version",
-            "attn_jvp_workspace_bytes"} <= set(names)
+    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_rmsnorm_fwd",
+            "attn_jvp_strerror", "attn_jvp_version", "attn_jvp_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -78,6 +78,19 @@ def _call(lib, ptrs=None, dims=(1, 1, 8, 8, 128), scale=0.1, opts=None):
     if opts is None:
         return lib.attn_jvp_fwd(*args)
     return lib.attn_jvp_fwd_ex(*args, ctypes.byref(opts))
+
+
+def test_set_up_failure_launches_nothing(lib):
+    """With no usable device every precondition check passes and the first set-up call (the device query, made
+    before any enqueue) fails: the call must come back with LAUNCH_FAILED, not crash, having launched nothing.
+    Only meaningful where no GPU is visible; skipped on a GPU machine (there the pointers would be dereferenced)."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible: fake pointers would reach a kernel")
+    from paper_2510_08431_amd.binding import AttnJvpOpts
+    assert _call(lib) == 5
+    o = AttnJvpOpts(); o.workspace = 0x10000; o.workspace_bytes = 1 << 30
+    assert _call(lib, dims=(1, 1, 256, 4096, 128), opts=o) == 5                  # fp16 value path: eight kernels, none enqueued
 
 
 def test_argument_validation_returns_codes_without_launching(lib):
