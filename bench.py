@@ -188,8 +188,9 @@ def main():
     tflops = cfg.flops / (ms_per_step * 1e-3) / 1e12
     kern_tflops = cfg.flops / (kern_avg_ms * 1e-3) / 1e12
 
-    # Outside the timed region: the same workload through attn_jvp_fwd, the plain 15-argument call, which takes no
-    # workspace from the caller and therefore runs the hi + lo bf16-pair kernel.
+    # Outside the timed region: the same workload through the two entry points that take no workspace from the caller.
+    # attn_jvp_fwd (the plain 15-argument call) runs the hi + lo bf16-pair kernel; attn_jvp_fwd_static runs the same
+    # kernels as the timed steps on the library's static scratch array (if the shape fits it).
     other_entries = {}
     if not f32 and args.variant == "default" and layout == binding.LAYOUT_BHLD and not args.null_kv_tangents:
         def timed(fn, reps):
@@ -206,6 +207,9 @@ def main():
         with torch.cuda.stream(torch.cuda.default_stream(dev)):
             other_entries["attn_jvp_fwd"] = dict(timed(lambda: binding.attn_jvp_fwd(
                 t["q"], t["k"], t["v"], t["tq"], tk, tv, cfg.scale, out=(o, to, lse)), reps), workspace="none (bf16 pairs)")
+        if binding.attn_jvp_workspace_bytes(B, H, Lq, Lkv, d) <= binding.attn_jvp_static_scratch_bytes():
+            other_entries["attn_jvp_fwd_static"] = dict(timed(lambda: binding.attn_jvp_fwd_static(
+                t["q"], t["k"], t["v"], t["tq"], tk, tv, cfg.scale, out=(o, to, lse)), reps), workspace="library's static array")
 
     traffic = None
     try:

@@ -16,7 +16,8 @@
  *
  * Memory: every pointer is a DEVICE pointer owned by the caller; the library allocates
  * nothing.  What it keeps between calls is cached per device at first use: the compute-unit
- * count and the raised dynamic-LDS limits of its kernels.  They need no workspace; if the
+ * count, the raised dynamic-LDS limits of its kernels and the address of the static scratch
+ * array of attn_jvp_fwd_static.  attn_jvp_fwd and attn_jvp_fwd_ex need no workspace; if the
  * caller lends one (attn_jvp_opts.workspace, see attn_jvp_workspace_bytes) the bf16 kernel
  * uses its faster fp16-value path (6 instead of 9 matrix products per key block).
  *   q, tq        [B, H, Lq,  d]  contiguous, row-major, d fastest (or [B, Lq, H, d], see attn_jvp_opts.layout)
@@ -35,9 +36,9 @@
  *
  * Execution: a call validates its arguments on the host, enqueues its kernels on the given
  * HIP stream and returns without synchronising.  A return value of 0 means "enqueued".
- * Codes 1-4 come from the host-side checks: nothing was launched and the outputs are
+ * Codes 1-4 and 6 come from the host-side checks: nothing was launched and the outputs are
  * untouched.  Everything else that can fail without a launch (device query, LDS limits, grid
- * sizes) is also done before the first enqueue and returns
+ * sizes, the static scratch's address) is also done before the first enqueue and returns
  * ATTN_JVP_LAUNCH_FAILED with nothing launched.  Only when the HIP runtime refuses an enqueue
  * in the middle of a call (the fp16 value path enqueues up to eight kernels) may earlier
  * kernels of that call already be on the stream; the outputs are then unspecified.  No
@@ -60,6 +61,10 @@ extern "C" {
 #define ATTN_JVP_UNSUPPORTED   3  /* head dim / dtype / kernel choice not built */
 #define ATTN_JVP_MISALIGNED    4  /* a pointer is not 16-byte aligned */
 #define ATTN_JVP_LAUNCH_FAILED 5  /* the HIP runtime refused a set-up call or a launch */
+#define ATTN_JVP_TOO_LARGE     6  /* attn_jvp_fwd_static only: the shape needs more than ATTN_JVP_STATIC_SCRATCH_BYTES */
+
+/* size of the library's static device scratch array (attn_jvp_fwd_static): 200 MiB per GPU */
+#define ATTN_JVP_STATIC_SCRATCH_BYTES (200u << 20)
 
 /* attn_jvp_opts.in_dtype / out_dtype */
 #define ATTN_JVP_BF16 0
@@ -146,7 +151,8 @@ typedef struct attn_jvp_opts {
  * This call passes no workspace, so at d = 128 it runs the hi + lo bf16-pair kernel: 9 matrix products per key
  * block where the fp16 value path runs 6, i.e. about 1.35x the time on long key sequences (measured on the
  * 32760-token self-attention shape, B = 1, H = 12: 20.5-21.3 ms against 15.2-16.4 ms; 37-38 % against 48-52 % of the
- * bf16 matrix peak).  Callers that want the faster path lend a workspace through attn_jvp_fwd_ex.
+ * bf16 matrix peak).  Callers that want the faster path lend a workspace through attn_jvp_fwd_ex, or call
+ * attn_jvp_fwd_static, which brings its own.
  */
 int attn_jvp_fwd(const void* q, const void* k, const void* v,
                  const void* tq, const void* tk, const void* tv,
@@ -159,6 +165,30 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v,
                     void* o, void* to, float* lse,
                     int B, int H, int Lq, int Lkv, int d, float scale,
                     const attn_jvp_opts* opts);
+
+/*
+ * attn_jvp_fwd_ex with the library's own scratch in place of a caller-lent workspace: for callers that cannot
+ * allocate device memory (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
+ * The scratch is a static device array of ATTN_JVP_STATIC_SCRATCH_BYTES (200 MiB: enough for the fp16 value path
+ * up to B*H*Lkv = 409 000 keys at d = 128, e.g. the 32760-token shape with 12 heads); every GPU the library is
+ * used on holds its copy from the first use until the process ends.  The call allocates nothing (no hipMalloc,
+ * no hipFree, no allocating library routine) and is otherwise attn_jvp_fwd_ex: same arguments, same kernels, same
+ * results bit for bit as attn_jvp_fwd_ex with a workspace of attn_jvp_workspace_bytes(...).
+ * opts may be NULL (defaults); opts->workspace must be NULL (ATTN_JVP_UNSUPPORTED otherwise).  Shapes whose
+ * attn_jvp_workspace_bytes(...) exceeds the array are rejected with ATTN_JVP_TOO_LARGE before anything is
+ * launched.  All calls on one GPU share that GPU's array: calls whose work overlaps in time (different
+ * streams, different host threads) race on it and must be serialised by the caller; calls on one stream are
+ * ordered and safe.  The array keeps the last call's contents; the kernels re-initialise what they read
+ * (statistics, tile flags and tickets are cleared by the call's own first kernels).
+ */
+int attn_jvp_fwd_static(const void* q, const void* k, const void* v,
+                        const void* tq, const void* tk, const void* tv,
+                        void* o, void* to, float* lse,
+                        int B, int H, int Lq, int Lkv, int d, float scale,
+                        const attn_jvp_opts* opts);
+
+/* ATTN_JVP_STATIC_SCRATCH_BYTES as the loaded library was built with. */
+size_t attn_jvp_static_scratch_bytes(void);
 
 /*
  * Bytes of scratch the MFMA kernel can use for this shape (0 if it has no use for any).  d = 128: the fp16 value

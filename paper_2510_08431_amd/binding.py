@@ -53,6 +53,10 @@ def load_library():
     lib.attn_jvp_fwd.restype = ci
     lib.attn_jvp_fwd_ex.argtypes = common + [ctypes.POINTER(AttnJvpOpts)]
     lib.attn_jvp_fwd_ex.restype = ci
+    lib.attn_jvp_fwd_static.argtypes = common + [ctypes.POINTER(AttnJvpOpts)]
+    lib.attn_jvp_fwd_static.restype = ci
+    lib.attn_jvp_static_scratch_bytes.argtypes = []
+    lib.attn_jvp_static_scratch_bytes.restype = ctypes.c_size_t
     lib.attn_jvp_strerror.argtypes = [ci]
     lib.attn_jvp_strerror.restype = ctypes.c_char_p
     lib.attn_jvp_version.argtypes = []
@@ -139,7 +143,8 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     None: zero key/value tangents (cross-attention onto a context without tangent); tq, tk, tv all None: plain
     attention forward, the returned `to` is None.
     out: optional (o, to, lse) to write into.  workspace: "auto" (a cached per-device torch buffer), None (no
-    scratch: the kernel then uses its bf16-pair path) or a uint8 CUDA tensor.  layout=LAYOUT_BLHD: all eight
+    scratch: the kernel then uses its bf16-pair path), a uint8 CUDA tensor, or "static" (the C entry point
+    attn_jvp_fwd_static: the library's own static device array; with `out` given the call allocates nothing).  layout=LAYOUT_BLHD: all eight
     tensors are [B, L, H, d] instead (lse stays [B, H, Lq]).  timing_events: optional pair of
     torch.cuda.Event(enable_timing=True) that the library records right before and after the main kernel.
     Returns (o, to, lse); asynchronous.
@@ -168,6 +173,9 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     opts.flags = int(flags)
     opts.layout = int(layout)
     entry = lib.attn_jvp_fwd_ex
+    if isinstance(workspace, str) and workspace == "static":
+        entry = lib.attn_jvp_fwd_static
+        workspace = None
     if isinstance(workspace, str) and workspace == "auto":
         need = lib.attn_jvp_workspace_bytes(B, H, Lq, Lkv, d) if q.dtype == torch.bfloat16 else 0
         workspace = _workspace(q.device, stream, need) if need else None
@@ -185,6 +193,18 @@ def attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=None, out_dtype=torch.float3
     if rc != 0:
         raise AttnJvpError(rc, attn_jvp_strerror(rc))
     return o, to, lse
+
+
+def attn_jvp_static_scratch_bytes():
+    return int(load_library().attn_jvp_static_scratch_bytes())
+
+
+def attn_jvp_fwd_static(q, k, v, tq, tk, tv, scale, out, **kw):
+    """The C entry point `attn_jvp_fwd_static`: as attn_jvp_fwd_ex, with the library's static device scratch in
+    place of a workspace.  `out` = (o, to, lse) is required, so that nothing is allocated on the way."""
+    if out is None:
+        raise ValueError("attn_jvp_fwd_static writes into caller-provided outputs: pass out=(o, to, lse)")
+    return attn_jvp_fwd_ex(q, k, v, tq, tk, tv, scale, out=out, workspace="static", **kw)
 
 
 def attn_jvp_rmsnorm_fwd(x, tx, w, eps, out=None, stream=None):

@@ -1,5 +1,5 @@
 // C-ABI entry points: argument validation, kernel choice, launch.  No allocation; the only state is what is cached
-// per device at first use (compute-unit count, raised LDS limits).
+// per device at first use (compute-unit count, raised LDS limits, the address of the static scratch array).
 #include "../../include/attn_jvp.h"
 #include "launchers.h"
 #include <cmath>
@@ -10,11 +10,17 @@
 
 using attn_jvp::Problem;
 
+// Scratch of attn_jvp_fwd_static: device memory that belongs to the library.  Every GPU the library runs on holds its own
+// copy of this array, at its own address, from the first use until the process ends.  The name below is a host-side
+// stand-in, not a device address: host code only ever uses the per-device pointer hipGetSymbolAddress returns.
+static __device__ __align__(256) unsigned char scratch[ATTN_JVP_STATIC_SCRATCH_BYTES];
+
 namespace attn_jvp {
 namespace {
 constexpr int MAX_DEVICES = 64;
 std::mutex g_setup_mutex;
 int g_cus[MAX_DEVICES];                         // 0 = not queried yet
+void* g_scratch[MAX_DEVICES];                   // device address of `scratch` on each device, null = not looked up yet
 std::set<std::pair<const void*, int>> g_lds_set;   // (kernel, device) pairs whose dynamic-LDS limit has been raised
 }  // namespace
 
@@ -42,6 +48,23 @@ hipError_t ensure_dynamic_lds(const void* kern, int bytes, int dev) {
     return e;
 }
 
+// Address of the static scratch array on the current device (looked up once per device, with that device current).
+static hipError_t static_scratch(void** ptr) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_setup_mutex);
+    if (g_scratch[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr || (reinterpret_cast<uintptr_t>(p) & 255u)) return hipErrorInvalidSymbol;
+        g_scratch[dev] = p;
+    }
+    *ptr = g_scratch[dev];
+    return hipSuccess;
+}
 }  // namespace attn_jvp
 
 namespace {
@@ -50,7 +73,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 
 int run(const void* q, const void* k, const void* v, const void* tq, const void* tk, const void* tv,
         void* o, void* to, float* lse, int B, int H, int Lq, int Lkv, int d, float scale,
-        const attn_jvp_opts* opts) {
+        const attn_jvp_opts* opts, bool use_static_scratch = false) {
     attn_jvp_opts def = {};
     def.in_dtype = ATTN_JVP_BF16;
     def.out_dtype = ATTN_JVP_OUT_FP32;
@@ -77,6 +100,15 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
 
     void* workspace = opts->workspace;
     size_t workspace_bytes = opts->workspace ? opts->workspace_bytes : 0;
+    if (use_static_scratch) {
+        if (opts->workspace) return ATTN_JVP_UNSUPPORTED;      // this entry point brings its own scratch
+        const size_t need = opts->in_dtype == ATTN_JVP_BF16 ? attn_jvp_workspace_bytes(B, H, Lq, Lkv, d) : 0;
+        if (need > (size_t)ATTN_JVP_STATIC_SCRATCH_BYTES) return ATTN_JVP_TOO_LARGE;
+        if (need > 0) {
+            if (attn_jvp::static_scratch(&workspace) != hipSuccess) return ATTN_JVP_LAUNCH_FAILED;
+            workspace_bytes = ATTN_JVP_STATIC_SCRATCH_BYTES;
+        }
+    }
 
     Problem p{q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale,
               opts->in_dtype, opts->out_dtype, static_cast<hipStream_t>(opts->stream), opts->flags,
@@ -117,6 +149,14 @@ int attn_jvp_fwd_ex(const void* q, const void* k, const void* v, const void* tq,
     return run(q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale, opts);
 }
 
+int attn_jvp_fwd_static(const void* q, const void* k, const void* v, const void* tq, const void* tk, const void* tv,
+                        void* o, void* to, float* lse, int B, int H, int Lq, int Lkv, int d, float scale,
+                        const attn_jvp_opts* opts) {
+    return run(q, k, v, tq, tk, tv, o, to, lse, B, H, Lq, Lkv, d, scale, opts, true);
+}
+
+size_t attn_jvp_static_scratch_bytes(void) { return ATTN_JVP_STATIC_SCRATCH_BYTES; }
+
 int attn_jvp_rmsnorm_fwd(const void* x, const void* tx, const float* w, void* y, void* ty,
                          long long rows, int d, float eps, int dtype, void* stream) {
     if (!x || !tx || !w || !y || !ty) return ATTN_JVP_NULL_PTR;
@@ -147,6 +187,7 @@ const char* attn_jvp_strerror(int code) {
         case ATTN_JVP_UNSUPPORTED: return "unsupported head dim, dtype, kernel choice or option";
         case ATTN_JVP_MISALIGNED: return "a pointer is not 16-byte aligned";
         case ATTN_JVP_LAUNCH_FAILED: return "the HIP runtime refused a set-up call or the kernel launch";
+        case ATTN_JVP_TOO_LARGE: return "the shape needs more scratch than the library's static array holds";
         default: return "unknown attn_jvp error code";
     }
 }

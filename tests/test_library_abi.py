@@ -27,7 +27,7 @@ def declared_functions():
 
 def test_header_symbols_exported(lib):
     names = declared_functions()
-    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_rmsnorm_fwd",
+    assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_fwd_static", "attn_jvp_static_scratch_bytes", "attn_jvp_rmsnorm_fwd",
             "attn_jvp_strerror", "attn_jvp_version", "attn_jvp_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
@@ -68,16 +68,40 @@ def test_workspace_bytes(lib):
 
 def test_version_and_strerror(lib):
     assert lib.attn_jvp_version() >= 100
-    msgs = [lib.attn_jvp_strerror(c).decode() for c in range(0, 7)]
-    assert msgs[0] == "ok" and len(set(msgs)) == 7 and all(msgs)
+    msgs = [lib.attn_jvp_strerror(c).decode() for c in range(0, 8)]
+    assert msgs[0] == "ok" and len(set(msgs)) == 8 and all(msgs)
 
 
-def _call(lib, ptrs=None, dims=(1, 1, 8, 8, 128), scale=0.1, opts=None):
+def _call(lib, ptrs=None, dims=(1, 1, 8, 8, 128), scale=0.1, opts=None, static=False):
     p = [0x1000 * (i + 1) for i in range(9)] if ptrs is None else ptrs
     args = [ctypes.c_void_p(x) for x in p] + list(dims) + [ctypes.c_float(scale)]
+    if static:
+        return lib.attn_jvp_fwd_static(*args, ctypes.byref(opts) if opts is not None else None)
     if opts is None:
         return lib.attn_jvp_fwd(*args)
     return lib.attn_jvp_fwd_ex(*args, ctypes.byref(opts))
+
+
+def test_static_entry_point_rejects_on_the_host(lib):
+    """attn_jvp_fwd_static: the limit of its scratch array, a caller workspace and the common argument checks are
+    all refused before anything touches a device (fake addresses, no GPU needed)."""
+    from paper_2510_08431_amd.binding import AttnJvpOpts
+    limit = lib.attn_jvp_static_scratch_bytes()
+    assert limit == 200 << 20
+    lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
+    assert lib.attn_jvp_workspace_bytes(1, 12, 32760, 32760, 128) <= limit      # the headline shape fits
+    assert lib.attn_jvp_workspace_bytes(1, 40, 75600, 75600, 128) > limit
+    assert _call(lib, dims=(1, 40, 75600, 75600, 128), static=True) == 6         # TOO_LARGE
+    assert _call(lib, dims=(1, 13, 32760, 32760, 128), static=True) == 6
+    o = AttnJvpOpts(); o.workspace = 0x10000; o.workspace_bytes = 1 << 20        # brings its own scratch: refused
+    assert _call(lib, opts=o, static=True) == 3
+    good = [0x1000 * (i + 1) for i in range(9)]
+    p = list(good); p[0] = 0
+    assert _call(lib, p, static=True) == 1
+    p = list(good); p[2] += 8
+    assert _call(lib, p, static=True) == 4
+    assert _call(lib, dims=(1, 1, 0, 8, 128), static=True) == 2
+    assert _call(lib, dims=(1, 1, 8, 8, 48), static=True) == 3
 
 
 def test_set_up_failure_launches_nothing(lib):
@@ -91,6 +115,7 @@ def test_set_up_failure_launches_nothing(lib):
     assert _call(lib) == 5
     o = AttnJvpOpts(); o.workspace = 0x10000; o.workspace_bytes = 1 << 30
     assert _call(lib, dims=(1, 1, 256, 4096, 128), opts=o) == 5                  # fp16 value path: eight kernels, none enqueued
+    assert _call(lib, dims=(1, 1, 256, 4096, 128), static=True) == 5
 
 
 def test_argument_validation_returns_codes_without_launching(lib):
