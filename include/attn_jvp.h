@@ -118,6 +118,12 @@ extern "C" {
                                      nothing checks at run time: workgroup w of a launch runs on XCD w mod 8, and
                                      the GPU is otherwise idle.  If it does not hold, only speed is lost. */
 
+#define ATTN_JVP_FLAG_NO_RESIDENT 16 /* MFMA kernel only: launch one workgroup per 128-row query tile and let the hardware hand
+                                     them out, instead of one resident workgroup per compute unit that walks through
+                                     its share of the tiles (the default from two tiles per compute unit on).
+                                     Results are identical.  For callers that run other kernels on the same GPU at
+                                     the same time: resident workgroups assume they get a compute unit each. */
+
 typedef struct attn_jvp_opts {
     int    in_dtype;        /* ATTN_JVP_BF16 or ATTN_JVP_FP32: dtype of q, k, v, tq, tk, tv */
     int    out_dtype;       /* ATTN_JVP_OUT_FP32 or ATTN_JVP_OUT_INPUT: dtype of o, to */

@@ -92,7 +92,7 @@ int run(const void* q, const void* k, const void* v, const void* tq, const void*
     if (opts->out_dtype != ATTN_JVP_OUT_FP32 && opts->out_dtype != ATTN_JVP_OUT_INPUT) return ATTN_JVP_UNSUPPORTED;
     if (opts->layout != ATTN_JVP_LAYOUT_BHLD && opts->layout != ATTN_JVP_LAYOUT_BLHD) return ATTN_JVP_UNSUPPORTED;
     if (opts->reserved != 0) return ATTN_JVP_UNSUPPORTED;
-    if (opts->flags & ~(ATTN_JVP_FLAG_FAST | ATTN_JVP_FLAG_NO_F16 | ATTN_JVP_FLAG_F16_ALWAYS | ATTN_JVP_FLAG_NO_LOCKSTEP)) return ATTN_JVP_UNSUPPORTED;
+    if (opts->flags & ~(ATTN_JVP_FLAG_FAST | ATTN_JVP_FLAG_NO_F16 | ATTN_JVP_FLAG_F16_ALWAYS | ATTN_JVP_FLAG_NO_LOCKSTEP | ATTN_JVP_FLAG_NO_RESIDENT)) return ATTN_JVP_UNSUPPORTED;
     if (opts->workspace && (reinterpret_cast<uintptr_t>(opts->workspace) & 255u)) return ATTN_JVP_MISALIGNED;
     const void* ptrs[] = {q, k, v, tq, tk, tv, o, to, lse};   // (NULL passes the alignment test)
     for (const void* p : ptrs)

@@ -16,7 +16,8 @@
 // into two rings of 4 stages each (K|tK: 16 KiB per stage, V|tV: 16 KiB per stage, 128 KiB in all), K four
 // blocks and V three blocks ahead of the block being accumulated, XOR-swizzled so that both the row-wise
 // 128-bit reads (K, tK as MFMA A operand) and the transposing 64-bit reads (V, tV) spread over all banks.
-// Q and tQ fragments stay in registers (in the AGPR half of the file: only MFMA instructions read them).
+// Q and tQ fragments stay in registers (in the AGPR half of the file: only MFMA instructions read them); they reach
+// them through LDS, and the results leave through LDS, so that every global load and store moves whole rows.
 //
 // Software pipeline inside a wavefront (there is one wavefront per SIMD, so matrix and vector work
 // overlap only through the order of issue, fixed here by scheduling fences): the score MFMAs of block
@@ -55,19 +56,15 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 constexpr int D = 128, BR = 128, BC = 32, NSTAGE = 4, NTHREADS = 256;
 constexpr int ROW_BYTES = D * 2;
 constexpr int TENSOR_BYTES = BC * ROW_BYTES;            // one tensor's block: 8 KiB
-#ifndef ATTN_JVP_PRESCAN_BLOCKS
-#define ATTN_JVP_PRESCAN_BLOCKS 16
-#endif
-constexpr int PRESCAN_BLOCKS = ATTN_JVP_PRESCAN_BLOCKS;   // key blocks sampled for the fp16 path's exponent reference
+constexpr int PRESCAN_BLOCKS = NSTAGE;   // key blocks sampled for the fp16 path's exponent reference: the first four, which start the K ring anyway
 constexpr int KV_STAGE_BYTES = 2 * TENSOR_BYTES;        // K|tK or V|tV
 constexpr int V_RING_BASE = NSTAGE * KV_STAGE_BYTES;    // K ring at [0, 64 KiB), V ring at [64 KiB, 128 KiB)
 constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
-static_assert(PRESCAN_BLOCKS >= 4 && PRESCAN_BLOCKS % 2 == 0 && PRESCAN_BLOCKS * TENSOR_BYTES <= LDS_BYTES && 2 * PRESCAN_BLOCKS + 16 < 64,
-              "the samples share the ring area, and their loads plus the Q fetch must fit the 6-bit vmcnt counter");
 
 // nothing may be scheduled across a fence: the instruction order between fences is the issue order
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -241,19 +238,23 @@ constexpr int ONLINE_MIN_BLOCKS = 160;     // (ATTN_JVP_FLAG_F16_ALWAYS sets thi
 constexpr int LOCKSTEP_MIN_BLOCKS = 1024;            // tiles of at least 1.3 ms: a wasted wait is at most 8 % of one
 constexpr unsigned long long LOCKSTEP_WAIT_TICKS = 10000;   // 100 us of the 100 MHz wall clock
 constexpr int LOCKSTEP_MAX_POLLS = 2048;
+constexpr int STAGGER_TICKS = 32;   // start offset between neighbouring resident workgroups of an XCD (0.32 us; 31 steps = 10 us)
 constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
 
 // TAN selects which tangents exist: TAN_ALL (tQ, tK, tV), TAN_QUERY (tQ only: "ZT" below, zero key/value tangents)
 // or TAN_NONE (plain attention forward, O and lse only: 2 of the 6 products; same code path, nothing else changes).
 constexpr int TAN_NONE = 0, TAN_QUERY = 1, TAN_ALL = 2;
 
+// One query tile (128 rows of one head), start to finish.  `vw` is the tile's index in the launch's list of
+// (head, query tile) pairs as a one-workgroup-per-tile launch would number its workgroups; n_tiles their count.
 template <int MODE, int TAN>
-__global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
+__device__ __forceinline__ void attn_jvp_tile(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     void* __restrict__ O, void* __restrict__ tO, float* __restrict__ LSE,
     int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
-    int H, int blhd, int out_bf16, int d_out, int out_blhd, int online_min_blocks, int lockstep_slots) {
+    int H, int blhd, int out_bf16, int d_out, int out_blhd, int online_min_blocks, int lockstep_slots,
+    const int vw, const int n_tiles) {
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16 || MODE == MODE_F16_ONLINE;   // fp16 weights and value operands
     constexpr bool PRESCAN = MODE == MODE_F16;                          // fixed reference from a key sample
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // those; the online fp16 kernel works on exactly the tiles flagged 1 and sets 3 (done), or 2 if it has to
     // abandon one itself; the bf16-pair kernel, given the flags, works on exactly the tiles flagged 2.
     if constexpr (ONLINE) {
-        if (wg_flags[blockIdx.x] != 1) return;
+        if (wg_flags[vw] != 1) return;
         // Lock-step start of the tiles that share an XCD's L2 (lockstep_slots = workgroups an XCD holds at a time, 0 =
         // off).  The tiles of this tier take different times (moves of the reference), and over many rounds of
         // tiles the workgroups of an XCD drift apart until each streams K and V from memory on its own.  Each
@@ -275,7 +276,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         // partial round of a launch simply waits out the limit once.
         if (lockstep_slots > 0) {
             if (threadIdx.x == 0) {
-                int* ticket = wg_flags + (((int)gridDim.x * 4 + 255) & ~255) / 4 + (blockIdx.x & 7) * 16;
+                int* ticket = wg_flags + ((n_tiles * 4 + 255) & ~255) / 4 + (vw & 7) * 16;
                 const int mine = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 const int full = (mine / lockstep_slots + 1) * lockstep_slots;
                 const unsigned long long t0 = wall_clock64();
@@ -288,13 +289,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             __syncthreads();
         }
     } else if constexpr (!F16) {
-        if (wg_flags != nullptr && wg_flags[blockIdx.x] != 2) return;
+        if (wg_flags != nullptr && wg_flags[vw] != 2) return;
     }
     extern __shared__ __attribute__((aligned(1024))) char smem[];
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // (an opaque copy of the thread index: with resident workgroups this function is the body of a loop over tiles, and
+    // everything derived from the lane id would otherwise be hoisted out of that loop and kept in registers across
+    // tiles, on top of what a tile needs anyway)
+    unsigned tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int c = lane & 31;          // query column of this lane in every MFMA result
     const int g = lane >> 5;          // which half of the contraction index this lane feeds
     // Workgroups are dealt to the 8 XCDs round-robin by index.  Give XCD x the x-th contiguous eighth of the
@@ -302,8 +308,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     // through the same L2: measured, this halves the kernel's HBM write traffic (0.81 -> 0.41 GB on the video
     // workload, the algorithmic 0.40) at unchanged run time.  (It does not reduce the K/V fetch traffic: a head's
     // K and V do not fit an L2, so every round of 32 co-resident workgroups streams them again either way.)
-    const int n_wg = gridDim.x;
-    const int bid = (n_wg & 7) == 0 ? (int)(blockIdx.x & 7) * (n_wg >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+    const int n_wg = n_tiles;
+    const int bid = (n_wg & 7) == 0 ? (vw & 7) * (n_wg >> 3) + (vw >> 3) : vw;
     const long bh = bid / q_tiles;
     const int q0 = (bid % q_tiles) * BR + wave * 32;
 
@@ -331,62 +337,34 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         issue_pair_clamped<true, !ZT>(Vh, tVh, v_stride, blk * BC, Lkv,
                                       lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
-    // start the rings while Q is being fetched (rows past the end are clamped, so all copies are unconditional);
-    // the fp16 path first scans a sample of the keys through the K ring (below) and starts the rings after that
-    auto start_rings = [&]() __attribute__((always_inline)) {
-        copy_k(0); copy_v(0); copy_k(1); copy_v(1); copy_k(2); copy_v(2); copy_k(3);
-    };
-    // fp16 path: the K rows of up to PRESCAN_BLOCKS evenly spaced key blocks (first and last included), sample i at
-    // LDS offset i * 8 KiB (the area the rings use later), all requested at once so that one memory latency
-    // covers them and the Q fetch
-    // Half as many below 8192 keys: a row's sample of 256 keys then sits as far below the row's true maximum (in
-    // standard deviations of the scores) as 512 keys do on the long sequences, and each sampled block costs a tile
-    // of a short sequence more (config 2, 4096 keys: 2.3 % of the step).
-    const int max_samples = n_blocks < 256 ? PRESCAN_BLOCKS / 2 : PRESCAN_BLOCKS;
-    const int ns = n_blocks < max_samples ? n_blocks : max_samples;
-    // (32-bit, divisors known at compile time: a 64-bit division by a run-time value is a hundred scalar
-    // instructions, and this is evaluated three times per sample)
-    auto sample_block = [&](int i) -> int {
-        if (n_blocks <= max_samples) return i;
-        const unsigned x = (unsigned)i * (unsigned)(n_blocks - 1);      // < 16 * 2^26
-        return (int)(max_samples == PRESCAN_BLOCKS ? x / (unsigned)(PRESCAN_BLOCKS - 1) : x / (unsigned)(PRESCAN_BLOCKS / 2 - 1));
-    };
-    if constexpr (PRESCAN) {
-        for (int i = 0; i < ns; ++i) {
-            const int blk = sample_block(i);
+    // Tile start.  One round trip to memory brings in K(0..3) (K ring, all four stages) and the tile's 128 rows of Q and
+    // tQ, which are staged through the V ring's area (64 KiB, not needed yet) so that they, too, come as whole
+    // rows: fetched straight into the MFMA operand layout, every load instruction of a wave would touch 32 rows with
+    // 32 bytes each, and the tile start took 4.7 us instead of one memory latency.  Staged like four 32-row K blocks
+    // per tensor (same swizzle), wave w then reads its rows (block w) with the K fragment addresses.  V(0..2) are
+    // requested once everyone has read its fragments (rows past the end are clamped, so all copies are unconditional).
+    constexpr uint32_t Q_STAGE = V_RING_BASE, TQ_STAGE = V_RING_BASE + 4 * TENSOR_BYTES;
+    const int qrow = q0 + c;
+    {
+        const char* Qh = reinterpret_cast<const char*>(Q) + q_base * 2;
+        const char* tQh = reinterpret_cast<const char*>(tQ) + q_base * 2;
+        const int tile_row0 = q0 - wave * 32;
+        copy_k(0); copy_k(1); copy_k(2); copy_k(3);
 #pragma unroll
-            for (int r = 0; r < 2; ++r) {
-                const int rowblk = wave * 2 + r;
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int rowblk = wave * 2 + i;
                 const int row = rowblk * 4 + (lane >> 4);
                 const int pc = lane & 15;
-                int grow = blk * BC + row;
-                grow = grow < Lkv ? grow : Lkv - 1;
-                ATTN_JVP_LOAD_LDS(Kh + (long)grow * k_stride + ((pc ^ (row & 15)) << 4),
-                                  lds0 + (uint32_t)i * TENSOR_BYTES + rowblk * 1024);
+                int grow = tile_row0 + 32 * j + row;
+                grow = grow < Lq ? grow : Lq - 1;
+                const long goff = (long)grow * k_stride + ((pc ^ (row & 15)) << 4);
+                ATTN_JVP_LOAD_LDS(Qh + goff, lds0 + Q_STAGE + (uint32_t)j * TENSOR_BYTES + rowblk * 1024);
+                if constexpr (!PRIMAL) ATTN_JVP_LOAD_LDS(tQh + goff, lds0 + TQ_STAGE + (uint32_t)j * TENSOR_BYTES + rowblk * 1024);
             }
-        }
-    } else {
-        start_rings();
     }
-
-    // Q^T / tQ^T as MFMA B operand: lane (c, g) holds row q0+c, elements 16t + 8g .. +7
-    const int qrow = q0 + c;
-    const int qrow_ld = qrow < Lq ? qrow : Lq - 1;
-    bf16x8 qf[8], tqf[8];
-    {
-        const bf16x8* qp = reinterpret_cast<const bf16x8*>(Q + q_base + (long)qrow_ld * row_elems + 8 * g);
-        const bf16x8* tqp = reinterpret_cast<const bf16x8*>(tQ + q_base + (long)qrow_ld * row_elems + 8 * g);
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-            qf[t] = qp[2 * t];
-            if constexpr (!PRIMAL) tqf[t] = tqp[2 * t];
-        }
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {   // keep them in accumulation registers: only MFMAs read them
-            asm volatile("" : "+a"(qf[t]));
-            if constexpr (!PRIMAL) asm volatile("" : "+a"(tqf[t]));
-        }
-    }
+    auto start_v_ring = [&]() __attribute__((always_inline)) { copy_v(0); copy_v(1); copy_v(2); };
 
     // per-lane LDS read addresses within stage 0 of the K ring / of the V ring; stage and tensor offsets are
     // 16-bit immediates of the read instructions
@@ -398,6 +376,25 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         const uint32_t rowpart = (4 * g + (i >> 2)) * ROW_BYTES + (2 * hb + ((i & 3) >> 1)) * 16 + 8 * (i & 1);
 #pragma unroll
         for (int db = 0; db < 4; ++db) vaddr0[db] = lds0 + V_RING_BASE + rowpart + ((db ^ (i >> 2)) << 6);
+    }
+
+    // Q^T / tQ^T as MFMA B operand: lane (c, g) holds row q0+c, elements 16t + 8g .. +7
+    bf16x8 qf[8], tqf[8];
+    {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // K(0..3), Q and tQ are in
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            qf[t] = lds_read_b128(kaddr0[t] + Q_STAGE + (uint32_t)wave * TENSOR_BYTES);
+            if constexpr (!PRIMAL) tqf[t] = lds_read_b128(kaddr0[t] + TQ_STAGE + (uint32_t)wave * TENSOR_BYTES);
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {   // keep them in accumulation registers: only MFMAs read them
+            asm volatile("" : "+a"(qf[t]));
+            if constexpr (!PRIMAL) asm volatile("" : "+a"(tqf[t]));
+        }
+        __syncthreads();                                    // everyone has its fragments: the V ring's area is free
+        if constexpr (!PRESCAN) start_v_ring();             // (the sampled-reference kernel first decides whether it takes the tile)
     }
 
     f32x16 accO[4], accAB[4];
@@ -597,8 +594,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     if constexpr (PRESCAN) {
         float sum1 = 0.f, sum2 = 0.f;   // first and second moment of the sampled raw scores (full blocks only)
         int n_stat = 0;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();                // every wave's share of the samples has landed
+        // the sample: K(0..3), which sit in the four stages of the K ring
+        const int ns = n_blocks < PRESCAN_BLOCKS ? n_blocks : PRESCAN_BLOCKS;
         // Two samples per step, software-pipelined: the sixteen fragment reads of a pair go out together, and the
         // MFMAs of pair p+1 run while the vector unit works through the statistics of pair p.
         auto scan_one = [&](const float (&x)[16], int blk) __attribute__((always_inline)) {
@@ -620,7 +617,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         };
         f32x16 s0, s1;
         auto scores_of_pair = [&](int i) __attribute__((always_inline)) {   // samples i and i+1 (or i twice)
-            const uint32_t off0 = (uint32_t)i * TENSOR_BYTES, off1 = (uint32_t)(i + 1 < ns ? i + 1 : i) * TENSOR_BYTES;
+            const uint32_t off0 = (uint32_t)i * KV_STAGE_BYTES, off1 = (uint32_t)(i + 1 < ns ? i + 1 : i) * KV_STAGE_BYTES;
             bf16x8 ka[8], kb[8];
 #pragma unroll
             for (int t = 0; t < 8; ++t) { ka[t] = lds_read_b128(kaddr0[t] + off0); kb[t] = lds_read_b128(kaddr0[t] + off1); }
@@ -640,8 +637,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             for (int e = 0; e < 16; ++e) asm volatile("" : "+v"(x0[e]), "+v"(x1[e]));   // copied out before s0, s1 are reused
             FENCE();
             if (i + 2 < ns) scores_of_pair(i + 2);
-            scan_one(x0, sample_block(i));
-            if (i + 1 < ns) scan_one(x1, sample_block(i + 1));
+            scan_one(x0, i);
+            if (i + 1 < ns) scan_one(x1, i + 1);
         }
         m_scan = xhalf_max(m_scan) * c2;
         // Is a fixed reference good enough for this row?  For scores with standard deviation sigma the maximum
@@ -664,24 +661,22 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
             // an outlying maximum would otherwise push the keys that carry its sum below the fp16 range.
             headroom = fminf(fmaxf(reach - 6.f, -6.f), REF_HEADROOM);
         }
-        __syncthreads();   // everyone is done with the samples before the ring copies overwrite them
+        // the workgroup's vote, through a word of the V ring's last stage (nothing is there yet; the K ring is live)
         volatile __attribute__((address_space(3))) int* flag =
-            (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds0;
-        if (threadIdx.x == 0) *flag = 0;
+            (volatile __attribute__((address_space(3))) int*)(uintptr_t)(lds0 + V_RING_BASE + 3 * KV_STAGE_BYTES);
+        if (tid == 0) *flag = 0;
         __syncthreads();
         if (__builtin_amdgcn_ballot_w64(risky) != 0 && lane == 0) *flag = 1;
         __syncthreads();
         const bool decline = *flag != 0;
         __syncthreads();
         if (decline) {                       // uniform over the workgroup; nothing is in flight
-            if (threadIdx.x == 0) wg_flags[blockIdx.x] = n_blocks >= online_min_blocks ? 1 : 2;
+            if (tid == 0) wg_flags[vw] = n_blocks >= online_min_blocks ? 1 : 2;
             return;
         }
-        start_rings();
+        start_v_ring();
     }
     {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // K(0..3), V(0..2) and the Q fragments are in
-        __syncthreads();
         plain_scores(0);
         if (n_blocks == 1) mask_scores(0);
         m = (PRESCAN ? m_scan : row_max()) + headroom;
@@ -697,6 +692,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         l_part = 0.f;
         r_part = 0.f;
         static_for<4>([&](auto J) { softmax_pair(J); });   // pairs 0-3 of block 0; pairs 4-7 follow in iteration 0
+        // V(0) and V(1) have landed (the first iteration reads V(0) before its own barrier, and publishes V(1) with
+        // it); the copies of V(2), issued last, may still be under way
+        if constexpr (ZT) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        __syncthreads();
     }
 
     // ---- online reference (MODE_F16_ONLINE).  Checked once per block, when the scores of block b+1 have been handed
@@ -989,7 +989,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         __syncthreads();                       // everyone is done with the rings
         volatile __attribute__((address_space(3))) int* flag =
             (volatile __attribute__((address_space(3))) int*)(uintptr_t)lds0;
-        if (threadIdx.x == 0) *flag = 0;
+        if (tid == 0) *flag = 0;
         __syncthreads();
         if (__builtin_amdgcn_ballot_w64(bad) != 0 && lane == 0) *flag = 1;
         __syncthreads();
@@ -997,8 +997,8 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         __syncthreads();
         if constexpr (F16) {
             // the fp16 kernels do not repair: they hand the tile to the launch that follows (online fp16, then bf16 pairs)
-            if (threadIdx.x == 0)
-                wg_flags[blockIdx.x] = redo ? (ONLINE || n_blocks < online_min_blocks ? 2 : 1) : (ONLINE ? 3 : 0);
+            if (tid == 0)
+                wg_flags[vw] = redo ? (ONLINE || n_blocks < online_min_blocks ? 2 : 1) : (ONLINE ? 3 : 0);
             if (redo) return;
         } else if (__builtin_expect(redo, 0)) {
             // ============================ safe sweep (rare) ============================
@@ -1057,16 +1057,20 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const float inv_l = 1.f / l_row;
     const float mu = r_row * inv_l;
     const float fo = gO * inv_l, ft = gAB * inv_l;
-    if (qrow < Lq) {
-        // Outputs: rows d_out elements wide in the caller's layout.  d_out = 128 unless the inputs are zero-padded
-        // copies of a smaller head dimension: then only the first d_out columns exist (and are stored).
-        const int o_row = out_blhd ? H * d_out : d_out;
-        const long o_base = out_blhd ? (bidx * Lq * H + hidx) * d_out : bh * (long)Lq * d_out;
-        const long out_off = o_base + (long)qrow * o_row + 4 * g;
-        float* Op = static_cast<float*>(O) + out_off;
-        float* tOp = static_cast<float*>(tO) + out_off;
-        uint16_t* Ob = static_cast<uint16_t*>(O) + out_off;       // bf16 outputs: same element offsets
-        uint16_t* tOb = static_cast<uint16_t*>(tO) + out_off;
+    // Outputs: rows d_out elements wide in the caller's layout.  d_out = 128 unless the inputs are zero-padded
+    // copies of a smaller head dimension: then only the first d_out columns exist (and are stored).
+    //
+    // A lane holds 16 scattered 16-byte pieces of ONE row per tensor, so storing from the accumulators directly puts
+    // only 32 contiguous bytes per row into each store instruction.  Measured, such a 128 KiB tile takes a compute
+    // unit 3.6 us to write (18 us when all units write at once), against 1.1 us (5.4 us) when every instruction
+    // writes whole rows.  Each wave therefore turns its 32 x 128 results round through its own 32 KiB of the (now
+    // idle) LDS: written as held (row c, 16-byte chunk 8 db + 2 v4 + g, at chunk position chunk ^ c so that neither
+    // direction meets bank conflicts), read back two whole rows per instruction.  LDS operations of one wave execute
+    // in order, so the wave needs no barrier of its own; the workgroup barrier at the end keeps the next tile's
+    // first copies (resident workgroups) off the staging areas of waves that are still reading.
+    {
+        typedef __attribute__((address_space(3))) f32x4 lds_float4;
+        const uint32_t stage_o = lds0 + (uint32_t)wave * 32768u, stage_t = stage_o + 16384u;
 #pragma unroll
         for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -1078,20 +1082,71 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
                 t4.y = (accAB[db][4 * v4 + 1] - mu * a1) * ft;
                 t4.z = (accAB[db][4 * v4 + 2] - mu * a2) * ft;
                 t4.w = (accAB[db][4 * v4 + 3] - mu * a3) * ft;
-                if (32 * db + 8 * v4 >= d_out) continue;      // uniform: a column of the padding
-                if (out_bf16) {      // uniform; four bf16 = 8 bytes per lane and tensor
-                    *reinterpret_cast<uint2*>(Ob + 32 * db + 8 * v4) = make_uint2(pack_bf16(o4.x, o4.y), pack_bf16(o4.z, o4.w));
-                    if constexpr (!PRIMAL)
-                        *reinterpret_cast<uint2*>(tOb + 32 * db + 8 * v4) = make_uint2(pack_bf16(t4.x, t4.y), pack_bf16(t4.z, t4.w));
-                } else {
-                    *reinterpret_cast<float4*>(Op + 32 * db + 8 * v4) = o4;
-                    if constexpr (!PRIMAL) *reinterpret_cast<float4*>(tOp + 32 * db + 8 * v4) = t4;
-                }
+                const uint32_t at = (uint32_t)c * 512u + (uint32_t)(((8 * db + 2 * v4 + g) ^ c) << 4);
+                *reinterpret_cast<lds_float4*>((uintptr_t)(stage_o + at)) = f32x4{o4.x, o4.y, o4.z, o4.w};
+                if constexpr (!PRIMAL) *reinterpret_cast<lds_float4*>((uintptr_t)(stage_t + at)) = f32x4{t4.x, t4.y, t4.z, t4.w};
             }
         // m carries `headroom` binades that l_row lacks: take them out of both before adding (exact scalings)
-        if (g == 0)
+        if (g == 0 && qrow < Lq)
             LSE[bh * Lq + qrow] = ((m - headroom) + __builtin_amdgcn_logf(l_row * __builtin_amdgcn_exp2f(headroom))) * 0.6931471805599453f;
+        const int o_row = out_blhd ? H * d_out : d_out;
+        const long o_base = out_blhd ? (bidx * Lq * H + hidx) * d_out : bh * (long)Lq * d_out;
+        const int chunk = lane & 31;                 // 16-byte chunk of the row this lane stores: columns 4 chunk .. +3
+        if (4 * chunk < d_out) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = 2 * i + g;             // row of the wave's 32
+                const int row = q0 + r;
+                const uint32_t at = (uint32_t)r * 512u + (uint32_t)((chunk ^ r) << 4);
+                const f32x4 ov = *reinterpret_cast<const lds_float4*>((uintptr_t)(stage_o + at));
+                f32x4 tv_ = ov;
+                if constexpr (!PRIMAL) tv_ = *reinterpret_cast<const lds_float4*>((uintptr_t)(stage_t + at));
+                const float4 o4 = make_float4(ov[0], ov[1], ov[2], ov[3]), t4 = make_float4(tv_[0], tv_[1], tv_[2], tv_[3]);
+                if (row < Lq) {
+                    const long off = o_base + (long)row * o_row + 4 * chunk;
+                    if (out_bf16) {      // uniform; four bf16 = 8 bytes per lane and tensor
+                        *reinterpret_cast<uint2*>(static_cast<uint16_t*>(O) + off) = make_uint2(pack_bf16(o4.x, o4.y), pack_bf16(o4.z, o4.w));
+                        if constexpr (!PRIMAL)
+                            *reinterpret_cast<uint2*>(static_cast<uint16_t*>(tO) + off) = make_uint2(pack_bf16(t4.x, t4.y), pack_bf16(t4.z, t4.w));
+                    } else {
+                        *reinterpret_cast<float4*>(static_cast<float*>(O) + off) = o4;
+                        if constexpr (!PRIMAL) *reinterpret_cast<float4*>(static_cast<float*>(tO) + off) = t4;
+                    }
+                }
+            }
+        }
+        __syncthreads();
     }
+}
+
+// The launch: workgroup w does tiles w, w + gridDim.x, w + 2 gridDim.x, ...  With one workgroup per tile (gridDim.x
+// = n_tiles) that is one tile each, handed out by the hardware as compute units fall free; with fewer, the workgroups
+// stay resident and walk through their tiles themselves: no workgroup launch between tiles, the tile-independent
+// set-up is done once, and a tile's output stores drain while the next tile's first loads are already queued
+// behind them.  A tile ends with every wave past a workgroup barrier that follows its last LDS read, on every
+// path, so the next tile may start filling LDS at once.  Since gridDim.x is then a multiple of 8, tile w + k gridDim.x
+// runs on the same XCD as tile w, as the tile map in attn_jvp_tile assumes.
+template <int MODE, int TAN>
+__global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
+    const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
+    const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
+    void* __restrict__ O, void* __restrict__ tO, float* __restrict__ LSE,
+    int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
+    int H, int blhd, int out_bf16, int d_out, int out_blhd, int online_min_blocks, int lockstep_slots, int n_tiles,
+    int stagger_ticks) {
+    // Resident workgroups all start together and their tiles take the same time, so without this every compute unit
+    // would write its 128 KiB of results in the same few microseconds, round after round, and wait for memory while
+    // the matrix pipes idle (measured 8 us per tile, against 1-2 us for a compute unit that writes alone).  The
+    // workgroups of an XCD therefore start stagger_ticks (of the 100 MHz wall clock) apart; the offsets persist, and
+    // each unit's stores fall into the others' sweeps.  Bounded by the clock; costs the last offset once per launch.
+    if (stagger_ticks > 0) {
+        const unsigned long long t0 = wall_clock64();
+        const unsigned long long wait = (unsigned long long)((blockIdx.x >> 3) & 31) * (unsigned)stagger_ticks;
+        while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(8);
+    }
+    for (int vw = blockIdx.x; vw < n_tiles; vw += gridDim.x)
+        attn_jvp_tile<MODE, TAN>(Q, K, V, tQ, tK, tV, O, tO, LSE, Lq, Lkv, scale, q_tiles, stats, wg_flags, H, blhd, out_bf16,
+                                 d_out, out_blhd, online_min_blocks, lockstep_slots, vw, n_tiles);
 }
 
 }  // namespace
@@ -1144,15 +1199,21 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     }
     const int q_tiles = (p.Lq + BR - 1) / BR;
     const long long blocks = (long long)q_tiles * p.B * p.H;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     int lockstep = 0;   // set for the online launch below
+    // The launch that does (nearly) all the tiles runs with resident workgroups, one per compute unit, each walking
+    // through its share of the tiles, when there are at least two tiles per unit; the hand-over launches, whose
+    // tiles differ in length or return at once, keep one workgroup per tile, which the hardware balances.
+    bool resident = false;
     auto launch = [&](auto kern, const void* v, const void* tv, const float* stats, int* wg_flags) -> hipError_t {
-        hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(NTHREADS), LDS_BYTES, p.stream,
+        const bool res = resident && cus % 8 == 0 && blocks >= 2LL * cus && !(p.flags & 16);   // 16: ATTN_JVP_FLAG_NO_RESIDENT
+        const long long grid = res ? cus : blocks;
+        const int stagger = res ? STAGGER_TICKS : 0;
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTHREADS), LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
                            p.o, p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout, p.out_dtype,
                            p.d_out, p.out_layout, (p.flags & 4) ? 0 : ONLINE_MIN_BLOCKS,   // F16_ALWAYS: never the pairs first
-                           lockstep);
+                           lockstep, (int)blocks, stagger);
         return hipGetLastError();
     };
     // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence
@@ -1175,8 +1236,10 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     // range), which it flags for the bf16-pair kernel; each returns at once from the tiles that are not its own.
     auto run = [&](auto tan, const void* tv, const void* tv16) -> hipError_t {
         constexpr int T = decltype(tan)::value;
+        resident = true;
         if (!f16) return launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T>, p.v, tv, nullptr, nullptr);
         hipError_t err = launch(attn_jvp_mfma_kernel<MODE_F16, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
+        resident = false;
         lockstep = ws.lockstep_slots;
         if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_F16_ONLINE, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
         lockstep = 0;
@@ -1188,6 +1251,7 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     } else if (p.tk == nullptr) {      // zero key/value tangents
         e = run(std::integral_constant<int, TAN_QUERY>{}, nullptr, nullptr);
     } else if (p.flags & 1) {
+        resident = true;
         e = launch(attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL>, p.v, p.tv, nullptr, nullptr);
     } else {
         e = run(std::integral_constant<int, TAN_ALL>{}, p.tv, ws.tv16);

@@ -151,7 +151,7 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.layout = 2                        # unknown layout
     assert _call(lib, opts=o) == 3
-    o = AttnJvpOpts(); o.flags = 16                        # unknown flag bit
+    o = AttnJvpOpts(); o.flags = 32                        # unknown flag bit
     assert _call(lib, opts=o) == 3
     o = AttnJvpOpts(); o.workspace = 0x10010; o.workspace_bytes = 1 << 20   # workspace not 256-byte aligned
     assert _call(lib, opts=o) == 4
