@@ -81,8 +81,8 @@ constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
 // through a pinned copy after the wait (the hand-over in phase 2), and the build checks the compiled assembly for
 // both kinds of accident (lint_mfma_asm.py).
 // `b` (a Q or tQ fragment) lives in accumulation registers.  SMFMA0 starts a chain (C = 0), SMFMA continues it.
-#define SMFMA0(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b))
-#define SMFMA(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b))
+#define SMFMA0(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "a"(a), "a"(b))
+#define SMFMA(a, b, c) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "a"(a), "a"(b))
 // 5 wait states of its own; the other 6 or more of the 11 are the instructions that follow in every instantiation
 // (LDS reads, the wait for the copies, the barrier, the first value MFMA) before the first hand-over copy: the
 // build's check of the compiled assembly counts them, so a schedule that came out shorter would fail the build.
@@ -421,7 +421,14 @@ __device__ __forceinline__ void attn_jvp_tile(
     uint32_t wp[8], wh[8];                              // P~^T, H~^T as packed bf16 pairs, result-register order
     uint32_t wpl[SPLIT ? 8 : 1], whl[SPLIT ? 8 : 1];    // their low-order parts
 
-    float sv[16], tsv[16];    // scores of the block whose softmax comes next, in ordinary registers
+    // Scores (raw, fp32) of two key blocks at a time, in ordinary registers: the score products of block b+1 write one
+    // pair of buffers while the softmax of block b still reads the other, so the scores are used where the matrix
+    // pipe delivers them and nothing is copied (block x lives in buffer x & 1).
+    f32x16 sbuf0, sbuf1, tsbuf0, tsbuf1;
+    auto SV = [&](auto Bc) __attribute__((always_inline)) -> f32x16& { if constexpr (decltype(Bc)::value == 0) return sbuf0; else return sbuf1; };
+    auto TSV = [&](auto Bc) __attribute__((always_inline)) -> f32x16& { if constexpr (decltype(Bc)::value == 0) return tsbuf0; else return tsbuf1; };
+    using B0 = std::integral_constant<int, 0>;
+    using B1 = std::integral_constant<int, 1>;
 
     // Softmax arithmetic of one pair of score elements (2j, 2j+1) -> packed weights, cut into five parts of at most
     // six vector instructions so that the pipelined sweep can put one part behind each MFMA:
@@ -429,14 +436,18 @@ __device__ __forceinline__ void attn_jvp_tile(
     //                 4: pack H~ (hi, lo)
     //   fp16 weights: 0: P~ = exp2(S c2 - m)   1: pack P~, H~ = P~16 (tS scale - ctr)   2: l += P~16   3: -
     //                 4: pack H~, r += H~16
-    float sp0, sp1, sh0, sh1;
+    f32x4 sp0a, sp1a;
+    float sh0, sh1;   // (the exponentials of pairs 0-3 are taken ahead of the rest of their softmax: one set per pair)
     float one = 1.f;   // kept in a scalar register as an opaque operand of the mixed multiply-adds
     asm volatile("" : "+s"(one));
-    auto softmax_part = [&](auto J, auto PART) __attribute__((always_inline)) {
+    auto softmax_part = [&](auto J, auto PART, auto Bc) __attribute__((always_inline)) {
         constexpr int j = decltype(J)::value, e = 2 * j, part = decltype(PART)::value;
+        const f32x16& sv = SV(Bc);
+        const f32x16& tsv = TSV(Bc);
+        constexpr int jj = j & 3;
         if constexpr (part == 0) {
-            sp0 = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
-            sp1 = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
+            sp0a[jj] = __builtin_amdgcn_exp2f(fmaf(sv[e], c2, -m));
+            sp1a[jj] = __builtin_amdgcn_exp2f(fmaf(sv[e + 1], c2, -m));
             // fp16 weights: everything downstream (l, H~, r) is formed from P~ AS ROUNDED to fp16, and r from H~ as
             // rounded, so that the result is the exact JVP of a softmax whose probabilities and centred tangent
             // scores are off by 2^-11 relative.  With unrounded values in l, r and H~ but rounded ones in the
@@ -444,14 +455,14 @@ __device__ __forceinline__ void attn_jvp_tile(
             // which is not small on peaked rows.  The mixed-precision multiply-adds read the packed halves
             // directly, so this costs no instruction.
         } else if constexpr (part == 1) {
-            if constexpr (F16) wp[j] = pack_f16(sp0, sp1);   // behind the scale-and-centre of part 1: the exponentials have landed
+            if constexpr (F16) wp[j] = pack_f16(sp0a[jj], sp1a[jj]);   // behind the scale-and-centre of part 1: the exponentials have landed
             if constexpr (!PRIMAL) {
                 if constexpr (F16) {
                     sh0 = mix_lo(wp[j], fmaf(tsv[e], scale_h, -ctr_h), 0.f);
                     sh1 = mix_hi(wp[j], fmaf(tsv[e + 1], scale_h, -ctr_h), 0.f);
                 } else {
-                    sh0 = sp0 * fmaf(tsv[e], scale_h, -ctr_h);
-                    sh1 = sp1 * fmaf(tsv[e + 1], scale_h, -ctr_h);
+                    sh0 = sp0a[jj] * fmaf(tsv[e], scale_h, -ctr_h);
+                    sh1 = sp1a[jj] * fmaf(tsv[e + 1], scale_h, -ctr_h);
                 }
             }
         } else if constexpr (part == 2) {
@@ -459,15 +470,15 @@ __device__ __forceinline__ void attn_jvp_tile(
                 l_part = mix_lo_s(wp[j], one, l_part);      // two chains: low halves, high halves
                 l_part2 = mix_hi_s(wp[j], one, l_part2);
             } else {
-                l_part += sp0 + sp1;
+                l_part += sp0a[jj] + sp1a[jj];
                 if constexpr (!PRIMAL) r_part += sh0 + sh1;
             }
         } else if constexpr (part == 3) {
             if constexpr (!F16) {
-                const uint32_t ph = pack_bf16(sp0, sp1);
+                const uint32_t ph = pack_bf16(sp0a[jj], sp1a[jj]);
                 wp[j] = ph;
                 if constexpr (SPLIT)   // lo = x - hi (exact in fp32), rounded to bf16
-                    wpl[j] = pack_bf16(sp0 - __uint_as_float(ph << 16), sp1 - __uint_as_float(ph & 0xffff0000u));
+                    wpl[j] = pack_bf16(sp0a[jj] - __uint_as_float(ph << 16), sp1a[jj] - __uint_as_float(ph & 0xffff0000u));
             }
         } else if constexpr (part == 4 && !PRIMAL) {
             const uint32_t hh = F16 ? pack_f16(sh0, sh1) : pack_bf16(sh0, sh1);
@@ -480,36 +491,60 @@ __device__ __forceinline__ void attn_jvp_tile(
             }
         }
     };
-    auto softmax_pair = [&](auto J) __attribute__((always_inline)) {
-        static_for<5>([&](auto PART) { softmax_part(J, PART); });
+    auto softmax_pair = [&](auto J, auto Bc) __attribute__((always_inline)) {
+        static_for<5>([&](auto PART) { softmax_part(J, PART, Bc); });
     };
     // the part(s) that go behind MFMA number `slot` of the `n_slots` a pair has to itself
-    auto softmax_slot = [&](auto J, auto SLOT, auto NSLOTS) __attribute__((always_inline)) {
+    auto softmax_slot = [&](auto J, auto SLOT, auto NSLOTS, auto Bc) __attribute__((always_inline)) {
         constexpr int slot = decltype(SLOT)::value, n_slots = decltype(NSLOTS)::value;
         if constexpr (n_slots >= 5) {
-            if constexpr (slot < 5) softmax_part(J, SLOT);
+            if constexpr (slot < 5) softmax_part(J, SLOT, Bc);
         } else if constexpr (n_slots == 4) {
-            if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{});
-            if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}); softmax_part(J, std::integral_constant<int, 2>{}); }
-            if constexpr (slot == 2) softmax_part(J, std::integral_constant<int, 3>{});
-            if constexpr (slot == 3) softmax_part(J, std::integral_constant<int, 4>{});
+            if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{}, Bc);
+            if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}, Bc); softmax_part(J, std::integral_constant<int, 2>{}, Bc); }
+            if constexpr (slot == 2) softmax_part(J, std::integral_constant<int, 3>{}, Bc);
+            if constexpr (slot == 3) softmax_part(J, std::integral_constant<int, 4>{}, Bc);
         } else if constexpr (n_slots == 3) {
-            if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{});
-            if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}); softmax_part(J, std::integral_constant<int, 3>{}); }
-            if constexpr (slot == 2) { softmax_part(J, std::integral_constant<int, 2>{}); softmax_part(J, std::integral_constant<int, 4>{}); }
+            if constexpr (slot == 0) softmax_part(J, std::integral_constant<int, 0>{}, Bc);
+            if constexpr (slot == 1) { softmax_part(J, std::integral_constant<int, 1>{}, Bc); softmax_part(J, std::integral_constant<int, 3>{}, Bc); }
+            if constexpr (slot == 2) { softmax_part(J, std::integral_constant<int, 2>{}, Bc); softmax_part(J, std::integral_constant<int, 4>{}, Bc); }
         } else if constexpr (n_slots == 1) {
-            if constexpr (slot == 0) static_for<5>([&](auto PART) { softmax_part(J, PART); });
+            if constexpr (slot == 0) static_for<5>([&](auto PART) { softmax_part(J, PART, Bc); });
         } else {
             static_assert(n_slots == 2, "a pair gets 1, 2, 3, 4 or at least 5 MFMA slots");
-            if constexpr (slot == 0) { softmax_part(J, std::integral_constant<int, 0>{}); softmax_part(J, std::integral_constant<int, 1>{}); }
+            if constexpr (slot == 0) { softmax_part(J, std::integral_constant<int, 0>{}, Bc); softmax_part(J, std::integral_constant<int, 1>{}, Bc); }
             if constexpr (slot == 1) {
-                softmax_part(J, std::integral_constant<int, 2>{}); softmax_part(J, std::integral_constant<int, 3>{});
-                softmax_part(J, std::integral_constant<int, 4>{});
+                softmax_part(J, std::integral_constant<int, 2>{}, Bc); softmax_part(J, std::integral_constant<int, 3>{}, Bc);
+                softmax_part(J, std::integral_constant<int, 4>{}, Bc);
             }
         }
     };
 
-    auto mask_scores = [&](int blk) __attribute__((always_inline)) {   // keys past Lkv: P~ = 0, tangent score 0
+    // parts 1-4 of a pair whose exponentials (part 0) were taken earlier, spread over the `n_slots` MFMAs of one value group
+    auto softmax_late_slot = [&](auto J, auto SLOT, auto NSLOTS, auto Bc) __attribute__((always_inline)) {
+        constexpr int slot = decltype(SLOT)::value, n_slots = decltype(NSLOTS)::value;
+        using P1 = std::integral_constant<int, 1>;
+        using P2 = std::integral_constant<int, 2>;
+        using P3 = std::integral_constant<int, 3>;
+        using P4 = std::integral_constant<int, 4>;
+        if constexpr (n_slots >= 4) {
+            if constexpr (slot < 4) softmax_part(J, std::integral_constant<int, slot + 1>{}, Bc);
+        } else if constexpr (n_slots == 3) {
+            if constexpr (slot == 0) softmax_part(J, P1{}, Bc);
+            if constexpr (slot == 1) { softmax_part(J, P2{}, Bc); softmax_part(J, P3{}, Bc); }
+            if constexpr (slot == 2) softmax_part(J, P4{}, Bc);
+        } else if constexpr (n_slots == 2) {
+            if constexpr (slot == 0) { softmax_part(J, P1{}, Bc); softmax_part(J, P2{}, Bc); }
+            if constexpr (slot == 1) { softmax_part(J, P3{}, Bc); softmax_part(J, P4{}, Bc); }
+        } else {
+            static_assert(n_slots == 1, "a value group has 1, 2, 3 or at least 4 MFMAs");
+            if constexpr (slot == 0) { softmax_part(J, P1{}, Bc); softmax_part(J, P2{}, Bc); softmax_part(J, P3{}, Bc); softmax_part(J, P4{}, Bc); }
+        }
+    };
+
+    auto mask_scores = [&](int blk, auto Bc) __attribute__((always_inline)) {   // keys past Lkv: P~ = 0, tangent score 0
+        f32x16& sv = SV(Bc);
+        f32x16& tsv = TSV(Bc);
         const int jbase = blk * BC + 4 * g;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -517,7 +552,7 @@ __device__ __forceinline__ void attn_jvp_tile(
             if (jj >= Lkv) { sv[e] = -INFINITY; tsv[e] = 0.f; }
         }
     };
-    auto plain_scores = [&](uint32_t stage_off) __attribute__((always_inline)) {   // unscheduled: prologue, safe sweep
+    auto plain_scores = [&](uint32_t stage_off, auto Bc) __attribute__((always_inline)) {   // unscheduled: prologue, safe sweep
         f32x16 s, ts;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
@@ -528,12 +563,16 @@ __device__ __forceinline__ void attn_jvp_tile(
             if constexpr (!PRIMAL) ts = MFMA(kf, tqf[t], ts);
             if constexpr (!ZT) ts = MFMA(lds_read_b128(kaddr0[t] + stage_off + TENSOR_BYTES), qf[t], ts);
         }
-#pragma unroll
-        for (int e = 0; e < 16; ++e) { sv[e] = s[e]; tsv[e] = ts[e]; }
+        SV(Bc) = s;
+        TSV(Bc) = ts;
+        // (in arithmetic registers from here on: the pipelined sweep carries these buffers round its loop, and a value
+        // that enters the loop in accumulation registers is kept there, with copies in and out at every turn)
+        asm volatile("" : "+v"(SV(Bc)), "+v"(TSV(Bc)));
     };
     // Row maximum of the 16 scores a lane holds, times c2.  Written with the three-operand maximum as assembly: the
     // compiler's own fmaxf first canonicalises every operand it did not produce itself (one extra v_max per score).
-    auto row_max = [&]() __attribute__((always_inline)) -> float {
+    auto row_max = [&](auto Bc) __attribute__((always_inline)) -> float {
+        const f32x16& sv = SV(Bc);
         auto max3 = [](float a, float b, float c) __attribute__((always_inline)) {
             float d;
             asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
@@ -599,10 +638,12 @@ __device__ __forceinline__ void attn_jvp_tile(
         // Two samples per step, software-pipelined: the sixteen fragment reads of a pair go out together, and the
         // MFMAs of pair p+1 run while the vector unit works through the statistics of pair p.
         auto scan_one = [&](const float (&x)[16], int blk) __attribute__((always_inline)) {
+            f32x16& sv = SV(B1{});      // (as scratch: the sweep has not started)
+            f32x16& tsv = TSV(B1{});
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sv[e] = x[e]; tsv[e] = 0.f; }
             if ((blk + 1) * BC > Lkv) {
-                mask_scores(blk);
+                mask_scores(blk, B1{});
             } else {
                 float a1 = 0.f, a2 = 0.f;
 #pragma unroll
@@ -677,9 +718,11 @@ __device__ __forceinline__ void attn_jvp_tile(
         start_v_ring();
     }
     {
-        plain_scores(0);
-        if (n_blocks == 1) mask_scores(0);
-        m = (PRESCAN ? m_scan : row_max()) + headroom;
+        plain_scores(0, B0{});
+        if (n_blocks == 1) mask_scores(0, B0{});
+        m = (PRESCAN ? m_scan : row_max(B0{})) + headroom;
+        const f32x16& sv = SV(B0{});
+        const f32x16& tsv = TSV(B0{});
         float lb = 0.f, rb = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
@@ -691,7 +734,7 @@ __device__ __forceinline__ void attn_jvp_tile(
         ctr_h = lb_row > 0.f ? xhalf_sum(rb) / lb_row : 0.f;
         l_part = 0.f;
         r_part = 0.f;
-        static_for<4>([&](auto J) { softmax_pair(J); });   // pairs 0-3 of block 0; pairs 4-7 follow in iteration 0
+        static_for<4>([&](auto J) { softmax_pair(J, B0{}); });   // pairs 0-3 of block 0; pairs 4-7 follow in iteration 0
         // V(0) and V(1) have landed (the first iteration reads V(0) before its own barrier, and publishes V(1) with
         // it); the copies of V(2), issued last, may still be under way
         if constexpr (ZT) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
@@ -708,8 +751,10 @@ __device__ __forceinline__ void attn_jvp_tile(
     // old frame, and are rescaled at the end of the iteration.  Rare: a cold path.
     bool pend = false;
     float pend_alpha = 1.f, pend_da = 0.f;
-    auto online_check = [&]() __attribute__((always_inline)) {
-        const float mb = row_max();
+    auto online_check = [&](auto Bc) __attribute__((always_inline)) {
+        const f32x16& sv = SV(Bc);
+        const f32x16& tsv = TSV(Bc);
+        const float mb = row_max(Bc);
         const bool upd = mb > (m - REF_HEADROOM) + ONLINE_SLACK;
         if (__builtin_expect(__builtin_amdgcn_ballot_w64(upd) != 0, 0)) {
             const float m_new = upd ? mb + REF_HEADROOM : m;
@@ -812,9 +857,11 @@ __device__ __forceinline__ void attn_jvp_tile(
 
     // Vector work is spread so that no MFMA has more than ~6 vector instructions behind it (beyond that the single
     // wavefront of a SIMD stops overlapping them with the matrix pipe):
-    //   phase 1 of iteration b  : weights of pairs 4-7 of block b   (scores fetched in phase 2 of iteration b-1)
-    //   phase 2, groups 0-3     : fetch of block b+1's scores (two pairs per group)
-    //   phase 2, groups 4-7     : weights of pairs 0-3 of block b+1 (their registers were consumed by groups 0-3)
+    //   phase 1 of iteration b  : weights of pairs 4-7 of block b   (its scores were produced in iteration b-1)
+    //   phase 2, groups 0-3     : exponentials of pairs 0-3 of block b+1 (one pair per group), straight from the
+    //                             registers its score products wrote in phase 1
+    //   phase 2, groups 4-7     : rest of the softmax of those pairs, which writes the packed weights (their
+    //                             registers were consumed by groups 0-3)
     auto iteration = [&](auto Uc, auto FULLc, int b) __attribute__((always_inline)) {
         constexpr int U = decltype(Uc)::value;
         constexpr bool FULL = decltype(FULLc)::value;
@@ -825,23 +872,26 @@ __device__ __forceinline__ void attn_jvp_tile(
         using K1 = std::integral_constant<int, (U + 1) & 3>;    // K stage of block b+1
         using K2 = std::integral_constant<int, (U + 2) & 3>;    // K stage of block b+2
         using V0 = std::integral_constant<int, U>;              // V stage of block b
-        f32x16 s, ts;
+        using Bcur = std::integral_constant<int, U & 1>;        // score buffers of block b
+        using Bnext = std::integral_constant<int, (U + 1) & 1>; // ... of block b+1, written in phase 1
+        f32x16& s = SV(Bnext{});
+        f32x16& ts = TSV(Bnext{});
         // ---- phase 1
         static_for<8>([&](auto T) {
             constexpr int t = decltype(T)::value;
             using J = std::integral_constant<int, 4 + t / 2>;
             constexpr int s0 = (t % 2) * PRODUCTS;
             if constexpr (t == 0) SMFMA0(kfr[t % KRING], qf[t], s); else SMFMA(kfr[t % KRING], qf[t], s);
-            softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{});
+            softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{}, Bcur{});
             FENCE();
             if constexpr (!PRIMAL) {
                 if constexpr (t == 0) SMFMA0(kfr[t % KRING], tqf[t], ts); else SMFMA(kfr[t % KRING], tqf[t], ts);
-                softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{});
+                softmax_slot(J{}, std::integral_constant<int, s0 + 1>{}, NS_P1{}, Bcur{});
                 FENCE();
             }
             if constexpr (!ZT) {
                 SMFMA(tkfr[t % KRING], qf[t], ts);
-                softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{});
+                softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{}, Bcur{});
                 FENCE();
             }
             if constexpr (t + KPRE < 8) read_k(std::integral_constant<int, t + KPRE>{}, K1{});
@@ -861,11 +911,6 @@ __device__ __forceinline__ void attn_jvp_tile(
         static_for<8>([&](auto Gc) {
             constexpr int gi = decltype(Gc)::value;     // group = (t2, db)
             constexpr int t2 = gi >> 2, db = gi & 3;
-            if constexpr (gi == 4 && !FULL) {
-                // tail iterations only: keys past Lkv (a ragged last block, or the unused block past the end)
-                if ((b + 2) * BC > Lkv) mask_scores(b + 1);
-            }
-            if constexpr (gi == 4 && ONLINE) online_check();
             const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
             bf16x8 hb8 = pb;
             if constexpr (!PRIMAL) hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
@@ -873,26 +918,26 @@ __device__ __forceinline__ void attn_jvp_tile(
             auto behind = [&](auto SLOT) __attribute__((always_inline)) {
                 constexpr int slot = decltype(SLOT)::value;
                 if constexpr (gi < 4) {
-                    // scores of block b+1 out of the MFMA result registers: elements 4 gi .. 4 gi + 3
-                    // (the empty asm pins each copy to this point; otherwise the compiler sinks them all to their uses)
-                    constexpr int first = GROUP_MFMAS >= 3 ? 1 : 0;   // the two slots that carry the fetch
-                    auto fetch = [&](auto E0) __attribute__((always_inline)) {
-                        constexpr int e0 = decltype(E0)::value;
-                        sv[e0] = s[e0]; sv[e0 + 1] = s[e0 + 1];
-                        if constexpr (PRIMAL) {
-                            asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]));
-                        } else {
-                            tsv[e0] = ts[e0]; tsv[e0 + 1] = ts[e0 + 1];
-                            asm volatile("" : "+v"(sv[e0]), "+v"(sv[e0 + 1]), "+v"(tsv[e0]), "+v"(tsv[e0 + 1]));
+                    // first touch of block b+1's scores (behind the second MFMA of a group where there is one: the
+                    // score products' results have landed by then; the build's assembly check counts the wait states)
+                    constexpr int first = GROUP_MFMAS >= 3 ? 1 : 0;
+                    if constexpr (slot == first) {
+                        if constexpr (gi == 0) {
+                            // (every lane of the new scores counts as read here, used or not: the score products of the
+                            // last iteration's unused block past the end still write their registers, which must not
+                            // have been handed to something else in the meantime)
+                            if constexpr (PRIMAL) asm volatile("" : "+v"(s));
+                            else asm volatile("" : "+v"(s), "+v"(ts));
+                            if constexpr (!FULL) {
+                                // tail iterations only: keys past Lkv (a ragged last block, or the unused block past the end)
+                                if ((b + 2) * BC > Lkv) mask_scores(b + 1, Bnext{});
+                            }
+                            if constexpr (ONLINE) online_check(Bnext{});
                         }
-                    };
-                    if constexpr (GROUP_MFMAS == 1) {        // a single slot carries both halves
-                        if constexpr (slot == 0) { fetch(std::integral_constant<int, 4 * gi>{}); fetch(std::integral_constant<int, 4 * gi + 2>{}); }
-                    } else if constexpr (slot == first || slot == first + 1) {
-                        fetch(std::integral_constant<int, 4 * gi + 2 * (slot - first)>{});
+                        softmax_part(std::integral_constant<int, gi>{}, std::integral_constant<int, 0>{}, Bnext{});
                     }
                 } else {
-                    softmax_slot(std::integral_constant<int, gi - 4>{}, SLOT, NS_P2{});
+                    softmax_late_slot(std::integral_constant<int, gi - 4>{}, SLOT, NS_P2{}, Bnext{});
                 }
             };
             accO[db] = VMFMA(vfr[gi % VRING], pb, accO[db]);
@@ -1015,9 +1060,11 @@ __device__ __forceinline__ void attn_jvp_tile(
                 asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
                 __syncthreads();
                 copy_k(b + 1); copy_v(b + 1);
-                plain_scores(off);
-                if ((b + 1) * BC > Lkv) mask_scores(b);
-                const float tmax = row_max();
+                plain_scores(off, B0{});
+                if ((b + 1) * BC > Lkv) mask_scores(b, B0{});
+                const f32x16& sv = SV(B0{});
+                const f32x16& tsv = TSV(B0{});
+                const float tmax = row_max(B0{});
                 const float m_new = fmaxf(m, tmax);
                 const float alpha = __builtin_amdgcn_exp2f(m - m_new);
                 m = m_new;
@@ -1043,7 +1090,7 @@ __device__ __forceinline__ void attn_jvp_tile(
                         if constexpr (!PRIMAL) accAB[db][e] = fmaf(accAB[db][e], alpha, -da * accO[db][e]);
                         accO[db][e] *= alpha;
                     }
-                static_for<8>([&](auto P) { softmax_pair(P); });
+                static_for<8>([&](auto P) { softmax_pair(P, B0{}); });
                 plain_values(off);
             }
             asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
