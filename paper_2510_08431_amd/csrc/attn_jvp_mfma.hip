@@ -151,6 +151,12 @@ __device__ __forceinline__ float mix_hi_s(uint32_t h2, float b, float c) {
     asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(h2), "s"(b), "v"(c));
     return d;
 }
+// element-wise product of two packed fp16 pairs, each rounded to fp16 (denormal results kept)
+__device__ __forceinline__ uint32_t pk_mul_f16(uint32_t a, uint32_t b) {
+    uint32_t d;
+    asm("v_pk_mul_f16 %0, %1, %2" : "=v"(d) : "v"(a), "v"(b));
+    return d;
+}
 __device__ __forceinline__ bf16x8 as_bf16x8(uint32_t a, uint32_t b, uint32_t c, uint32_t d) {
     u32x4 u = {a, b, c, d};
     return __builtin_bit_cast(bf16x8, u);
@@ -437,7 +443,8 @@ __device__ __forceinline__ void attn_jvp_tile(
     //   fp16 weights: 0: P~ = exp2(S c2 - m)   1: pack P~, H~ = P~16 (tS scale - ctr)   2: l += P~16   3: -
     //                 4: pack H~, r += H~16
     f32x4 sp0a, sp1a;
-    float sh0, sh1;   // (the exponentials of pairs 0-3 are taken ahead of the rest of their softmax: one set per pair)
+    float sh0, sh1;
+    uint32_t uh;   // fp16 weights: the pair's centred, scaled tangent scores as packed fp16   // (the exponentials of pairs 0-3 are taken ahead of the rest of their softmax: one set per pair)
     float one = 1.f;   // kept in a scalar register as an opaque operand of the mixed multiply-adds
     asm volatile("" : "+s"(one));
     auto softmax_part = [&](auto J, auto PART, auto Bc) __attribute__((always_inline)) {
@@ -458,8 +465,8 @@ __device__ __forceinline__ void attn_jvp_tile(
             if constexpr (F16) wp[j] = pack_f16(sp0a[jj], sp1a[jj]);   // behind the scale-and-centre of part 1: the exponentials have landed
             if constexpr (!PRIMAL) {
                 if constexpr (F16) {
-                    sh0 = mix_lo(wp[j], fmaf(tsv[e], scale_h, -ctr_h), 0.f);
-                    sh1 = mix_hi(wp[j], fmaf(tsv[e + 1], scale_h, -ctr_h), 0.f);
+                    // H~16 = P~16 (x) u16, u = tS scale - ctr rounded to fp16 first: one packed multiply for the pair
+                    uh = pack_f16(fmaf(tsv[e], scale_h, -ctr_h), fmaf(tsv[e + 1], scale_h, -ctr_h));
                 } else {
                     sh0 = sp0a[jj] * fmaf(tsv[e], scale_h, -ctr_h);
                     sh1 = sp1a[jj] * fmaf(tsv[e + 1], scale_h, -ctr_h);
@@ -481,7 +488,8 @@ __device__ __forceinline__ void attn_jvp_tile(
                     wpl[j] = pack_bf16(sp0a[jj] - __uint_as_float(ph << 16), sp1a[jj] - __uint_as_float(ph & 0xffff0000u));
             }
         } else if constexpr (part == 4 && !PRIMAL) {
-            const uint32_t hh = F16 ? pack_f16(sh0, sh1) : pack_bf16(sh0, sh1);
+            uint32_t hh;
+            if constexpr (F16) hh = pk_mul_f16(wp[j], uh); else hh = pack_bf16(sh0, sh1);
             wh[j] = hh;
             if constexpr (SPLIT)
                 whl[j] = pack_bf16(sh0 - __uint_as_float(hh << 16), sh1 - __uint_as_float(hh & 0xffff0000u));
