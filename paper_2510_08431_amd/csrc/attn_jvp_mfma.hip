@@ -440,11 +440,11 @@ __device__ __forceinline__ void attn_jvp_tile(
     // six vector instructions so that the pipelined sweep can put one part behind each MFMA:
     //   bf16 weights: 0: P~ = exp2(S c2 - m)   1: H~ = P~ (tS scale - ctr)   2: row sums   3: pack P~ (hi, lo)
     //                 4: pack H~ (hi, lo)
-    //   fp16 weights: 0: P~ = exp2(S c2 - m)   1: pack P~, H~ = P~16 (tS scale - ctr)   2: l += P~16   3: -
-    //                 4: pack H~, r += H~16
-    f32x4 sp0a, sp1a;
+    //   fp16 weights: 0: P~ = exp2(S c2 - m)   1: pack P~16, pack u16 = tS scale - ctr   2, 3: -
+    //                 4: H~16 = P~16 x u16 (one packed multiply), l += P~16, r += H~16
+    f32x4 sp0a, sp1a;   // (the exponentials of pairs 0-3 are taken ahead of the rest of their softmax: one set per pair)
     float sh0, sh1;
-    uint32_t uh;   // fp16 weights: the pair's centred, scaled tangent scores as packed fp16   // (the exponentials of pairs 0-3 are taken ahead of the rest of their softmax: one set per pair)
+    uint32_t uh;        // fp16 weights: the pair's centred, scaled tangent scores as packed fp16
     float one = 1.f;   // kept in a scalar register as an opaque operand of the mixed multiply-adds
     asm volatile("" : "+s"(one));
     auto softmax_part = [&](auto J, auto PART, auto Bc) __attribute__((always_inline)) {
@@ -474,8 +474,10 @@ __device__ __forceinline__ void attn_jvp_tile(
             }
         } else if constexpr (part == 2) {
             if constexpr (F16) {
-                l_part = mix_lo_s(wp[j], one, l_part);      // two chains: low halves, high halves
-                l_part2 = mix_hi_s(wp[j], one, l_part2);
+                if constexpr (PRIMAL) {
+                    l_part = mix_lo_s(wp[j], one, l_part);      // two chains: low halves, high halves
+                    l_part2 = mix_hi_s(wp[j], one, l_part2);
+                }   // (with tangents: in part 4, between the packed product and the sums that read it)
             } else {
                 l_part += sp0a[jj] + sp1a[jj];
                 if constexpr (!PRIMAL) r_part += sh0 + sh1;
@@ -489,7 +491,13 @@ __device__ __forceinline__ void attn_jvp_tile(
             }
         } else if constexpr (part == 4 && !PRIMAL) {
             uint32_t hh;
-            if constexpr (F16) hh = pk_mul_f16(wp[j], uh); else hh = pack_bf16(sh0, sh1);
+            if constexpr (F16) {
+                hh = pk_mul_f16(wp[j], uh);
+                l_part = mix_lo_s(wp[j], one, l_part);      // two chains: low halves, high halves
+                l_part2 = mix_hi_s(wp[j], one, l_part2);
+            } else {
+                hh = pack_bf16(sh0, sh1);
+            }
             wh[j] = hh;
             if constexpr (SPLIT)
                 whl[j] = pack_bf16(sh0 - __uint_as_float(hh << 16), sh1 - __uint_as_float(hh & 0xffff0000u));
@@ -825,17 +833,19 @@ __device__ __forceinline__ void attn_jvp_tile(
     auto read_k = [&](auto T, auto ST) __attribute__((always_inline)) {     // score step T of the block in K stage ST
         constexpr int t = decltype(T)::value;
         constexpr int off = decltype(ST)::value * KV_STAGE_BYTES;
-        kfr[t % KRING] = lds_read_b128(kaddr0[t] + off);
+        // (the tangent fragment first: LDS reads return in order, so the wait in front of the step's first product,
+        // which takes the K fragment, covers both and the third product needs none of its own)
         if constexpr (!ZT) tkfr[t % KRING] = lds_read_b128(kaddr0[t] + off + TENSOR_BYTES);
+        kfr[t % KRING] = lds_read_b128(kaddr0[t] + off);
     };
     auto read_v = [&](auto G, auto ST) __attribute__((always_inline)) {     // value group G of the block in V stage ST
         constexpr int gi = decltype(G)::value;
         constexpr int t2 = gi >> 2, db = gi & 3;
         constexpr int off = decltype(ST)::value * KV_STAGE_BYTES + t2 * 16 * ROW_BYTES;
-        vfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off), lds_read_tr_b64(vaddr0[db] + off + 8 * ROW_BYTES));
         if constexpr (!ZT)
             tvfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES),
                                        lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES + 8 * ROW_BYTES));
+        vfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off), lds_read_tr_b64(vaddr0[db] + off + 8 * ROW_BYTES));
     };
 
     // The copies of iteration b: K(b+4) into K stage b & 3, V(b+3) into V stage (b+3) & 3, as 8 direct-to-LDS
