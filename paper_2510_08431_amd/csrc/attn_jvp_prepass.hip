@@ -1,6 +1,8 @@
 // Pre-pass of the fp16 value path: per-head statistics, then V, tV -> scaled fp16 copies in the workspace.
-// Both kernels are memory-bound single passes (coalesced 128-bit accesses); together they move
-// 2 (Lq + 3 Lkv) d + 4 Lkv d bytes per head, a few percent of the main kernel's time on long sequences.
+// Two memory-bound launches (coalesced 128-bit accesses).  The first reads V and tV once (their largest magnitudes
+// fix the scales of the fp16 copies) and every 16th row of Q, tQ, K, tK (their row norms only steer how the tangent
+// weights are scaled; an estimate is enough, see f16_scales.h), and leaves one partial result per block; the second
+// reduces a head's partials, converts, and clears the lock-step tickets.  No atomics, nothing to zero beforehand.
 #include "launchers.h"
 #include "f16_scales.h"
 #include <hip/hip_bf16.h>
@@ -23,11 +25,6 @@ __device__ __forceinline__ uint4 ld16(const __hip_bfloat16* p) {
     return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
-__global__ void zero_stats_kernel(float* stats, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) stats[i] = 0.f;
-}
-
 struct StatsArgs {
     const __hip_bfloat16* x[6];   // V, tV, Q, tQ, K, tK
     int L[6];
@@ -39,62 +36,104 @@ __device__ __forceinline__ long row_offset(long bh, int row, int L, int H, int b
     return blhd ? (((bh / H) * L + row) * H + bh % H) * (long)D : (bh * L + row) * (long)D;
 }
 
-// One launch for all six tensors: blockIdx.z selects the tensor.  Slot 0, 1: abs max of V, tV; slots 2..5: largest
-// squared row norm of Q, tQ, K, tK.
-__global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __restrict__ stats) {
+constexpr int NORM_ROW_STEP = 16;   // row norms of Q, tQ, K, tK are taken from every 16th row (and the last one)
+
+// One launch for all six tensors: blockIdx.z selects the tensor, blockIdx.x a range of ROWS_PER_BLOCK rows.
+// Slot 0, 1: abs max of V, tV over every element; slots 2..5: largest squared row norm of Q, tQ, K, tK over the
+// sampled rows.  Every block writes its result (zero for an empty range or an absent tensor) to
+// partials[(head * gridDim.x + blockIdx.x) * 8 + tensor]: nothing needs clearing, and no two blocks share a word.
+__global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __restrict__ partials) {
     const int which = blockIdx.z;
     const int L = a.L[which];
     const int row0 = blockIdx.x * ROWS_PER_BLOCK;
-    if (row0 >= L || a.x[which] == nullptr) return;   // absent tangents leave their statistic at zero
     const long bh = blockIdx.y;
+    float* out = partials + (bh * gridDim.x + blockIdx.x) * 8 + which;
+    if (row0 >= L || a.x[which] == nullptr) {         // absent tangents leave their statistic at zero
+        if (threadIdx.x == 0) *out = 0.f;
+        return;
+    }
     const __hip_bfloat16* __restrict__ X = a.x[which];
     const int sub = threadIdx.x & 15;            // 16 lanes x 16 B = one 256-byte row
     const int r_in = threadIdx.x >> 4;
     float best = 0.f;
-    for (int rr = r_in; rr < ROWS_PER_BLOCK; rr += 64) {
+    auto fold = [&](const uint4& w) {
+        const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
+        float v = 0.f;
+        if (which < 2) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v = fmaxf(v, fmaxf(fabsf(bf16_lo(ws[i])), fabsf(bf16_hi(ws[i]))));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { const float c = bf16_lo(ws[i]), e = bf16_hi(ws[i]); v = fmaf(c, c, fmaf(e, e, v)); }
+            // row norm^2: sum over the 16 lanes of the row
+            v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); v += __shfl_xor(v, 8);
+        }
+        best = fmaxf(best, v);
+    };
+    if (which < 2) {
+        for (int rr = r_in; rr < ROWS_PER_BLOCK; rr += 64) {
+            uint4 w[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {            // four independent 16-byte loads in flight per lane
+                const int row = row0 + rr + 16 * u;
+                w[u] = row < L ? ld16(X + row_offset(bh, row, L, a.H, a.blhd) + sub * 8) : make_uint4(0, 0, 0, 0);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) fold(w[u]);
+        }
+    } else {
+        // the block's 64 sampled rows (row0, row0 + 16, ...) in one round of four loads per lane, plus the tensor's
+        // last row, taken by the block whose range holds it
         uint4 w[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {            // four independent 16-byte loads in flight per lane
-            const int row = row0 + rr + 16 * u;
+        for (int u = 0; u < 4; ++u) {
+            const int row = row0 + NORM_ROW_STEP * (r_in + 16 * u);
             w[u] = row < L ? ld16(X + row_offset(bh, row, L, a.H, a.blhd) + sub * 8) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const uint32_t ws[4] = {w[u].x, w[u].y, w[u].z, w[u].w};
-            float v = 0.f;
-            if (which < 2) {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v = fmaxf(v, fmaxf(fabsf(bf16_lo(ws[i])), fabsf(bf16_hi(ws[i]))));
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) { const float c = bf16_lo(ws[i]), e = bf16_hi(ws[i]); v = fmaf(c, c, fmaf(e, e, v)); }
-                // row norm^2: sum over the 16 lanes of the row
-                v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); v += __shfl_xor(v, 8);
-            }
-            best = fmaxf(best, v);
-        }
+        for (int u = 0; u < 4; ++u) fold(w[u]);
+        if (L - 1 >= row0 && L - 1 < row0 + ROWS_PER_BLOCK && r_in == 0) fold(ld16(X + row_offset(bh, L - 1, L, a.H, a.blhd) + sub * 8));
     }
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) best = fmaxf(best, __shfl_xor(best, o));
-    // one atomic per block, not per wave: all blocks of a (head, tensor) pair hit the same address, and atomics to
-    // one address serialise in the L2 (with one per wave they, not the loads, set the kernel's run time)
     __shared__ float wave_best[4];
     if ((threadIdx.x & 63) == 0) wave_best[threadIdx.x >> 6] = best;
     __syncthreads();
-    // non-negative floats order like their bit patterns; NaN/inf inputs give a huge pattern and end in the fallback
-    if (threadIdx.x == 0) {
-        best = fmaxf(fmaxf(wave_best[0], wave_best[1]), fmaxf(wave_best[2], wave_best[3]));
-        atomicMax(reinterpret_cast<unsigned int*>(stats + bh * 8 + which), __float_as_uint(best));
-    }
+    if (threadIdx.x == 0) *out = fmaxf(fmaxf(wave_best[0], wave_best[1]), fmaxf(wave_best[2], wave_best[3]));
 }
 
+// Reduces the head's partial statistics (NaN in an input gives NaN here and ends in the bf16-pair fallback), leaves
+// them in stats[head * 8 ..] for the sweep kernels (block 0 of each head), clears the lock-step tickets (block 0 of
+// head 0), then converts its share of the head's V, tV rows.
 __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat16* __restrict__ V,
                                                              const __hip_bfloat16* __restrict__ tV,
-                                                             const float* __restrict__ stats, __half* __restrict__ V16,
+                                                             const float* __restrict__ partials, int n_partials,
+                                                             float* __restrict__ stats, float* __restrict__ tickets,
+                                                             __half* __restrict__ V16,
                                                              __half* __restrict__ tV16, long elems_per_head, float scale,
                                                              int Lkv, int H, int blhd) {
     const long bh = blockIdx.y;
-    const F16Scales sc = f16_scales(stats + bh * 8, scale);
+    __shared__ float head_stats[8];
+    if (threadIdx.x < 64) {          // lane t % 8 of the first wave takes statistic t % 8 of every 8th partial
+        const int which = threadIdx.x & 7;
+        float best = 0.f;
+        for (int p = threadIdx.x >> 3; p < n_partials; p += 8) {
+            const float v = partials[(bh * n_partials + p) * 8 + which];
+            best = (v > best || v != v) ? v : best;      // a NaN sticks
+        }
+#pragma unroll
+        for (int o = 8; o < 64; o <<= 1) {
+            const float other = __shfl_xor(best, o);
+            best = (other > best || other != other) ? other : best;
+        }
+        if (threadIdx.x < 8) {
+            head_stats[which] = which < 6 ? best : 0.f;
+            if (blockIdx.x == 0) stats[bh * 8 + which] = which < 6 ? best : 0.f;
+        }
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 128) tickets[threadIdx.x] = 0.f;
+    __syncthreads();
+    const F16Scales sc = f16_scales(head_stats, scale);
     const float gV = ldexpf(1.f, -sc.eV), gT = ldexpf(1.f, -sc.eA);
     const long base = bh * elems_per_head;
     for (long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < elems_per_head; i += (long)gridDim.x * blockDim.x * 8) {
@@ -121,13 +160,17 @@ __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat1
 
 namespace {
 struct Layout {
-    size_t stats_bytes, flags_bytes, vals_bytes;
+    size_t stats_bytes, flags_bytes, vals_bytes, partials_bytes;
+    int n_partials;     // blocks of ROWS_PER_BLOCK rows that cover the longer of the two sequences
 };
 Layout layout(int B, int H, int Lq, int Lkv, int d) {
     const size_t heads = (size_t)B * H;
     const size_t tiles = heads * (size_t)((Lq + MFMA_TILE_ROWS - 1) / MFMA_TILE_ROWS);
+    const int Lmax = Lq > Lkv ? Lq : Lkv;
+    const int np = (Lmax + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
-    return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)) + 512, up(heads * (size_t)Lkv * d * sizeof(__half))};
+    return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)) + 512, up(heads * (size_t)Lkv * d * sizeof(__half)),
+            up(heads * (size_t)np * 8 * sizeof(float)), np};
 }
 struct PadArgs {
     const __hip_bfloat16* src[6];   // q, k, v, tq, tk, tv (null = absent)
@@ -194,7 +237,7 @@ hipError_t launch_pad_inputs(const Problem& p, Problem* padded) {
 
 size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
     const Layout l = layout(B, H, Lq, Lkv, d);
-    return l.stats_bytes + l.flags_bytes + 2 * l.vals_bytes;
+    return l.stats_bytes + l.flags_bytes + 2 * l.vals_bytes + l.partials_bytes;
 }
 
 hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out) {
@@ -205,11 +248,9 @@ hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out) {
     int* wg_flags = reinterpret_cast<int*>(ws + l.stats_bytes);
     __half* V16 = reinterpret_cast<__half*>(ws + l.stats_bytes + l.flags_bytes);
     __half* tV16 = reinterpret_cast<__half*>(ws + l.stats_bytes + l.flags_bytes + l.vals_bytes);
-    const int n_stats = (int)(heads * 8);
-    hipLaunchKernelGGL(zero_stats_kernel, dim3((n_stats + 255) / 256), dim3(256), 0, p.stream, stats, n_stats);
+    float* partials = reinterpret_cast<float*>(ws + l.stats_bytes + l.flags_bytes + 2 * l.vals_bytes);
     // tickets of the online tier's lock-step start: 8 XCDs x one counter per 64 bytes, after the flags
     float* tickets = reinterpret_cast<float*>(ws + l.stats_bytes + l.flags_bytes - 512);
-    hipLaunchKernelGGL(zero_stats_kernel, dim3(1), dim3(256), 0, p.stream, tickets, 128);
     out->lockstep_slots = cus % 8 == 0 ? cus / 8 : 0;   // one workgroup per compute unit, eight XCDs
     StatsArgs sa;
     const void* xs[6] = {p.v, p.tv, p.q, p.tq, p.k, p.tk};
@@ -219,16 +260,14 @@ hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out) {
     }
     sa.H = p.H;
     sa.blhd = p.layout;
-    const int Lmax = p.Lq > p.Lkv ? p.Lq : p.Lkv;
     auto bf = [](const void* x) { return static_cast<const __hip_bfloat16*>(x); };
-    hipLaunchKernelGGL(head_stats_kernel, dim3((Lmax + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK, (unsigned)heads, 6), dim3(256), 0,
-                       p.stream, sa, stats);
+    hipLaunchKernelGGL(head_stats_kernel, dim3(l.n_partials, (unsigned)heads, 6), dim3(256), 0, p.stream, sa, partials);
     const long eph = (long)p.Lkv * p.d;
     int cx = (int)((eph / 8 + 255) / 256);
     if (cx > 512) cx = 512;
     if (cx < 1) cx = 1;
-    hipLaunchKernelGGL(convert_values_kernel, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), stats,
-                       V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
+    hipLaunchKernelGGL(convert_values_kernel, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), partials,
+                       l.n_partials, stats, tickets, V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
     out->stats = stats;
     out->wg_flags = wg_flags;
     out->v16 = V16;

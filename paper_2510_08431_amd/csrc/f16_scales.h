@@ -7,8 +7,11 @@
 //   H~16 = fp16(H~ * 2^(eV - eA))
 // so that the O accumulator holds 2^-eV O~ and the A+B accumulator holds 2^-eA (A + B).  eA is the smallest
 // exponent that keeps both |tV16| < 2^14 and |H~16| <= P~ * 2^8, using the Cauchy-Schwarz bound
-// |tS scale - ctr| <= 2 scale (|tq||k| + |q||tk|) for the tangent scores.  Everything smaller than the bound
-// only loses headroom, never correctness; the main kernel detects overflow (inf) and falls back.
+// |tS scale - ctr| <= 2 scale (|tq||k| + |q||tk|) for the tangent scores.  The row norms come from a sample of
+// the rows (every 16th and the last), so this is an estimate of that bound, which itself is loose by an order of
+// magnitude on ordinary data.  Scores smaller than it only lose headroom; should a tangent score exceed what the
+// scale allows, H~16 overflows to inf, which the main kernel detects at the end of its sweep, and the tile is redone
+// by the bf16-pair kernel: a wrong estimate costs time, never correctness.
 #pragma once
 #include <hip/hip_runtime.h>
 
