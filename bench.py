@@ -92,7 +92,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: video-DiT self-attention)")
     ap.add_argument("--variant", choices=["default", "bf16-pairs", "fast"], default="default",
-                    help="MFMA kernel variant: default (workspace lent by the binding: fp16 value path from 2048 keys "
+                    help="MFMA kernel variant: default (workspace lent by the binding: fp16 value path from 2048 keys, or 256 with many query tiles, "
                          "on, bf16 pairs below), bf16-pairs (no workspace), fast (single bf16 weights; outside the "
                          "tolerance on peaked rows)")
     ap.add_argument("--fast", action="store_true", help="same as --variant fast")
@@ -226,7 +226,7 @@ def main():
         arithmetic = "bf16 in, f32 vector ALU"
     elif args.variant == "fast":
         arithmetic = "bf16 in, bf16 MFMA (single bf16 weights), f32 accumulate"
-    elif args.variant == "bf16-pairs" or Lkv < 2048:
+    elif args.variant == "bf16-pairs" or not (Lkv >= 2048 or (Lkv >= 256 and B * H * ((Lq + 127) // 128) >= 4 * 256)):   # the library's rule
         arithmetic = "bf16 in, bf16 MFMA (weights as hi+lo bf16 pairs in the value products), f32 accumulate"
     else:
         arithmetic = "bf16 in, bf16 score MFMA + fp16 value MFMA (fp16 weights, V and tV as scaled fp16 copies), f32 accumulate"

@@ -102,7 +102,8 @@ extern "C" {
 
 #define ATTN_JVP_FLAG_NO_F16 2    /* MFMA kernel only: do not use the fp16 value path even if a workspace is given */
 #define ATTN_JVP_FLAG_F16_ALWAYS 4 /* MFMA kernel only: use the fp16 value path (given a workspace) for short key
-                                     sequences too; without it Lkv < 2048 takes the bf16 pairs, which are faster
+                                     sequences too; without it Lkv < 2048 (Lkv < 256 when the call has at least four
+                                     query tiles per compute unit) takes the bf16 pairs, which are faster
                                      there (the fp16 path's pre-pass and key sampling do not pay off), and so do
                                      tiles with widely spread scores below ~5k keys */
 
@@ -141,7 +142,8 @@ typedef struct attn_jvp_opts {
                                On this path the row sums are taken over the weights as rounded, so o, to are
                                the exact result for probabilities and tangent scores off by 2^-11 relative, and
                                lse carries the rounding of l (at most 2^-11 absolute).  Without a workspace, and for
-                               Lkv < 2048: hi + lo bf16 pairs everywhere (9 products, ~16-bit weights). */
+                               Lkv < 2048 (Lkv < 256 for calls with at least four 128-row query tiles per compute
+                               unit): hi + lo bf16 pairs everywhere (9 products, ~16-bit weights). */
     size_t workspace_bytes; /* size of `workspace` */
     void*  timing_events[2]; /* optional hipEvent_t pair (created by the caller, with timing enabled), or NULL:
                                [0] is recorded on `stream` immediately before the main attention kernel and [1]

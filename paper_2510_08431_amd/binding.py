@@ -16,7 +16,7 @@ KERNEL_AUTO, KERNEL_FP32, KERNEL_MFMA = 0, 1, 2
 LAYOUT_BHLD = 0   # tensors are [B, H, L, d]
 LAYOUT_BLHD = 1   # tensors are [B, L, H, d] (lse stays [B, H, Lq])
 FLAG_FAST = 1     # MFMA kernel: P~ and H~ as single bf16 terms (6 matrix products per key block; not tolerance-safe)
-FLAG_F16_ALWAYS = 4   # MFMA kernel: fp16 value path also for Lkv < 2048 (given a workspace)
+FLAG_F16_ALWAYS = 4   # MFMA kernel: fp16 value path also for short key sequences (given a workspace)
 FLAG_NO_LOCKSTEP = 8   # MFMA kernel, running-reference fp16 tier: no lock-step start of the tiles of an XCD
 FLAG_NO_RESIDENT = 16   # MFMA kernel: one workgroup per query tile instead of resident workgroups
 FLAG_NO_F16 = 2   # MFMA kernel: hi + lo bf16 pairs (9 products) even when a workspace is available

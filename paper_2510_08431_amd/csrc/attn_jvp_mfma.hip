@@ -245,7 +245,11 @@ constexpr int LOCKSTEP_MIN_BLOCKS = 1024;            // tiles of at least 1.3 ms
 constexpr unsigned long long LOCKSTEP_WAIT_TICKS = 10000;   // 100 us of the 100 MHz wall clock
 constexpr int LOCKSTEP_MAX_POLLS = 2048;
 constexpr int STAGGER_TICKS = 32;   // start offset between neighbouring resident workgroups of an XCD (0.32 us; 31 steps = 10 us)
-constexpr int F16_MIN_KEYS = 2048;   // shorter key sequences take the bf16 pairs unless the caller insists
+// The fp16 path costs a pre-pass per call (two small launches, ~20 us plus the conversion of V and tV) and a key sample per
+// tile; per key block it is a quarter faster than the bf16 pairs.  It pays from 2048 keys on, and from 256 keys on when
+// the call has at least four tiles per compute unit to spread the pre-pass over (measured per tile, 12 tiles per unit:
+// 8 key blocks 24.8 against 27.9 us, 16 blocks 33.6 against 37.8 us); below that the bf16 pairs run unless the caller insists.
+constexpr int F16_MIN_KEYS = 2048, F16_MIN_KEYS_MANY_TILES = 256, F16_MANY_TILES_PER_CU = 4;
 
 // TAN selects which tangents exist: TAN_ALL (tQ, tK, tV), TAN_QUERY (tQ only: "ZT" below, zero key/value tangents)
 // or TAN_NONE (plain attention forward, O and lse only: 2 of the 6 products; same code path, nothing else changes).
@@ -636,9 +640,10 @@ __device__ __forceinline__ void attn_jvp_tile(
     //   bf16 weights: m = block-0 maximum + 40 binades; fine while later scores exceed it by < ~100 binades.
     //   fp16 weights: H~ (up to 2^8 P~ after scaling) must stay below 2^16, so P~ below 2^7, and the keys that carry
     //   the sum must stay inside the fp16 range below that (weights under 2^-25 round to zero), so m has to be close
-    //   to the true maximum: m = maximum over a sample of 16 evenly spaced key blocks (8 below 8192 keys; first and
-    //   last included) + (2.7 sigma - 6) binades, sigma = the row's sampled score spread: the true maximum, which
-    //   rarely exceeds the sampled one by more than 2.7 sigma, then gets a weight of at most 2^6.
+    //   to the true maximum: m = maximum over the first four key blocks (128 keys, which are in the K ring anyway)
+    //   + (2.7 sigma - 6) binades, sigma = the row's sampled score spread: the true maximum, which rarely exceeds
+    //   the sampled one by more than 2.7 sigma, then gets a weight of at most 2^6.  (If the first keys are not
+    //   typical of the rest, the end-of-sweep checks notice and the tile is redone with a running reference.)
     //   fp16 weights, online: m = running maximum + 1 binade, moved (with a rescale of everything accumulated)
     //   when a block's maximum exceeds the running one by more than ONLINE_SLACK: weights stay below 2^7, and
     //   keys more than 23 binades (16 nats) below the running maximum drop out of the fp16 range.
@@ -1284,7 +1289,8 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence
     // is long enough to amortise its per-call pre-pass and per-tile key sampling (measured break-even ~1500 keys)
     const bool f16 = !(p.flags & 3) && p.workspace != nullptr && (long long)p.B * p.H <= 65535 &&   // pre-pass grid.y
-                     (p.Lkv >= F16_MIN_KEYS || (p.flags & 4)) &&
+                     (p.Lkv >= F16_MIN_KEYS || (p.flags & 4) ||
+                      (p.Lkv >= F16_MIN_KEYS_MANY_TILES && blocks >= (long long)F16_MANY_TILES_PER_CU * cus)) &&
                      p.workspace_bytes >= f16_workspace_bytes(p.B, p.H, p.Lq, p.Lkv, p.d) &&
                      (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0;
     F16Workspace ws{};
