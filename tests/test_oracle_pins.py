@@ -217,9 +217,37 @@ def test_explicit_oracle(pin):
 
 
 @pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
-@pytest.mark.parametrize("Br,Bc", [(4, 3), (128, 64), (2, 5)])
-def test_streaming_oracle(pin, Br, Bc):
-    pin(lambda *a: alg2_head(*a, Br=Br, Bc=Bc))
+@pytest.mark.parametrize("Br,Bc,order", [(4, 3, "forward"), (128, 64, "forward"), (2, 5, "forward"), (4, 3, "tree"),
+                                         (5, 2, "backward")])
+def test_streaming_oracle(pin, Br, Bc, order):
+    pin(lambda *a: alg2_head(*a, Br=Br, Bc=Bc, order=order))
+
+
+def test_partial_states_merge_in_any_order():
+    """The rescale-and-add of Alg. 2's inner loop is an associative, commutative merge of per-block states: folding
+    the key blocks forward (the printed loop), backward, as a tree, or in a shuffled order gives the explicit
+    definition every time, also when a later block holds the row maxima (the rescale factors are then far from 1)."""
+    from oracle.alg2_stream import block_state, finish, merge
+    q, k, v, tq, tk, tv = rand_head(77, 9, 50, 8)
+    k[37] *= 6.0                                        # one key far above the rest for most rows
+    ref = attn_jvp_ref_head(q, k, v, tq, tk, tv, 0.4)
+    for order in ("forward", "backward", "tree"):
+        for x, y in zip(alg2_head(q, k, v, tq, tk, tv, 0.4, 4, 7, order=order), ref):
+            np.testing.assert_allclose(x, y, rtol=1e-12, atol=1e-13)
+    states = [block_state(q, tq, k[j:j + 6], v[j:j + 6], tk[j:j + 6], tv[j:j + 6], 0.4) for j in range(0, 50, 6)]
+    perm = np.random.default_rng(5).permutation(len(states))
+    acc = states[perm[0]]
+    for i in perm[1:]:
+        acc = merge(states[i], acc)
+    for x, y in zip(finish(acc), ref):
+        np.testing.assert_allclose(x, y, rtol=1e-12, atol=1e-13)
+    # a mistake in the merge must show: forgetting to rescale the tangent-side sums
+    def bad_merge(a, b):
+        good = merge(a, b)
+        return good[0], good[1], good[2], a[3] + b[3], good[4]
+    wrong = finish(bad_merge(states[0], bad_merge(states[1], states[7])))
+    right = finish(merge(states[0], merge(states[1], states[7])))
+    assert np.abs(wrong[1] - right[1]).max() > 1e-6
 
 
 # ---------------------------------------------------------------- mutants: every planted mistake must be caught
