@@ -58,13 +58,26 @@ typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
 typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int D = 128, BR = 128, BC = 32, NSTAGE = 4, NTHREADS = 256;
-constexpr int ROW_BYTES = D * 2;
-constexpr int TENSOR_BYTES = BC * ROW_BYTES;            // one tensor's block: 8 KiB
+constexpr int BR = 128, BC = 32, NSTAGE = 4, NTHREADS = 256;
+// Geometry for head dimension DH (128 or 64): LDS rows of DH bf16, a tensor's 32-row block, a ring stage (X | tX), the
+// two rings.  DH = 128: 256-byte rows, 8 KiB blocks, 128 KiB of LDS; DH = 64: half of each.
+template <int DH>
+struct Geo {
+    static_assert(DH == 128 || DH == 64, "head dimensions built natively");
+    static constexpr int ROW_BYTES = DH * 2;
+    static constexpr int TENSOR_BYTES = BC * ROW_BYTES;
+    static constexpr int KV_STAGE_BYTES = 2 * TENSOR_BYTES;        // K|tK or V|tV
+    static constexpr int V_RING_BASE = NSTAGE * KV_STAGE_BYTES;    // K ring first, V ring behind it
+    static constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
+    static constexpr int LANES_PER_ROW = ROW_BYTES / 16;           // 16-byte chunks of a row
+    static constexpr int ROWS_PER_COPY = 64 / LANES_PER_ROW;       // rows one direct-to-LDS instruction (64 x 16 B) moves
+    static constexpr int COPIES_PER_WAVE = BC / ROWS_PER_COPY / 4; // ... and how many of them a wave issues per tensor block
+    // swizzles, applied to the 16-byte chunk index of a row (on the global side of the copies): K, tK for row-wise
+    // 128-bit reads, V, tV for the transposing 64-bit reads
+    static __device__ __forceinline__ int k_swizzle(int row) { return DH == 128 ? (row & 15) : ((row >> 1) & 7); }
+    static __device__ __forceinline__ int v_swizzle(int row) { return DH == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
+};
 constexpr int PRESCAN_BLOCKS = NSTAGE;   // key blocks sampled for the fp16 path's exponent reference: the first four, which start the K ring anyway
-constexpr int KV_STAGE_BYTES = 2 * TENSOR_BYTES;        // K|tK or V|tV
-constexpr int V_RING_BASE = NSTAGE * KV_STAGE_BYTES;    // K ring at [0, 64 KiB), V ring at [64 KiB, 128 KiB)
-constexpr int LDS_BYTES = 2 * NSTAGE * KV_STAGE_BYTES;
 
 // nothing may be scheduled across a fence: the instruction order between fences is the issue order
 #define FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -183,37 +196,40 @@ __device__ __forceinline__ void load_lds_b128(const void* uniform_base, uint32_t
 #define ATTN_JVP_LOAD_LDS(g, l) load_lds_b128((g), __builtin_amdgcn_readfirstlane(l))
 
 // Copy one 32-row block of a tensor pair (X, tX) into an LDS stage (X at stage_base, tX TENSOR_BYTES above).
-// Each direct-to-LDS instruction moves 64 x 16 B = 4 rows; the LDS side is linear in the lane id, so the swizzle is
-// applied by choosing which 16-byte chunk of the row each lane fetches: K, tK: chunk ^= row & 15 (row-wise b128
-// reads); V, tV (VSWZ): chunk ^= (row & 3) << 2 (transposing b64 reads).  Rows past Lkv re-read the last valid
+// Each direct-to-LDS instruction moves 64 x 16 B = 4 rows of 256 bytes (8 of 128); the LDS side is linear in the lane
+// id, so the swizzle is applied by choosing which 16-byte chunk of the row each lane fetches (Geo::k_swizzle for K, tK:
+// row-wise b128 reads; Geo::v_swizzle (VSWZ) for V, tV: transposing b64 reads).  Rows past Lkv re-read the last valid
 // row (finite values; their scores are masked to -inf).
-template <bool VSWZ, bool WITH_TANGENT>
+template <int DH, bool VSWZ, bool WITH_TANGENT>
 __device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* tXh, long row_stride, int j0, int Lkv,
                                                    uint32_t stage_base, int wave, int lane) {
+    using G = Geo<DH>;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int rowblk = wave * 2 + i;
-        const int row = rowblk * 4 + (lane >> 4);
-        const int pc = lane & 15;
+    for (int i = 0; i < G::COPIES_PER_WAVE; ++i) {
+        const int rowblk = wave * G::COPIES_PER_WAVE + i;
+        const int row = rowblk * G::ROWS_PER_COPY + lane / G::LANES_PER_ROW;
+        const int pc = lane % G::LANES_PER_ROW;
         int grow = j0 + row;
         grow = grow < Lkv ? grow : Lkv - 1;
-        const long goff = (long)grow * row_stride + ((VSWZ ? (pc ^ ((row & 3) << 2)) : (pc ^ (row & 15))) << 4);
+        const long goff = (long)grow * row_stride + ((pc ^ (VSWZ ? G::v_swizzle(row) : G::k_swizzle(row))) << 4);
         const uint32_t dst = stage_base + rowblk * 1024;
         ATTN_JVP_LOAD_LDS(Xh + goff, dst);
-        if constexpr (WITH_TANGENT) ATTN_JVP_LOAD_LDS(tXh + goff, dst + TENSOR_BYTES);
+        if constexpr (WITH_TANGENT) ATTN_JVP_LOAD_LDS(tXh + goff, dst + G::TENSOR_BYTES);
     }
 }
 // Same copy for a block known to lie entirely inside the sequence: the per-lane byte offsets (row and swizzled
 // chunk) never change, so they are computed once and only the uniform block base advances.
 struct LaneOffsets { uint32_t k[2], v[2]; };
+template <int DH>
 __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int k_stride, int v_stride) {
-    LaneOffsets o;
+    using G = Geo<DH>;
+    LaneOffsets o = {};
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int row = (wave * 2 + i) * 4 + (lane >> 4);
-        const int pc = lane & 15;
-        o.k[i] = row * k_stride + ((pc ^ (row & 15)) << 4);
-        o.v[i] = row * v_stride + ((pc ^ ((row & 3) << 2)) << 4);
+    for (int i = 0; i < G::COPIES_PER_WAVE; ++i) {
+        const int row = (wave * G::COPIES_PER_WAVE + i) * G::ROWS_PER_COPY + lane / G::LANES_PER_ROW;
+        const int pc = lane % G::LANES_PER_ROW;
+        o.k[i] = row * k_stride + ((pc ^ G::k_swizzle(row)) << 4);
+        o.v[i] = row * v_stride + ((pc ^ G::v_swizzle(row)) << 4);
     }
     return o;
 }
@@ -257,7 +273,7 @@ constexpr int TAN_NONE = 0, TAN_QUERY = 1, TAN_ALL = 2;
 
 // One query tile (128 rows of one head), start to finish.  `vw` is the tile's index in the launch's list of
 // (head, query tile) pairs as a one-workgroup-per-tile launch would number its workgroups; n_tiles their count.
-template <int MODE, int TAN>
+template <int MODE, int TAN, int DH>
 __device__ __forceinline__ void attn_jvp_tile(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
@@ -265,6 +281,12 @@ __device__ __forceinline__ void attn_jvp_tile(
     int Lq, int Lkv, float scale, int q_tiles, const float* __restrict__ stats, int* __restrict__ wg_flags,
     int H, int blhd, int out_bf16, int d_out, int out_blhd, int online_min_blocks, int lockstep_slots,
     const int vw, const int n_tiles) {
+    using G = Geo<DH>;
+    constexpr int D = DH, ROW_BYTES = G::ROW_BYTES, TENSOR_BYTES = G::TENSOR_BYTES, KV_STAGE_BYTES = G::KV_STAGE_BYTES;
+    constexpr int V_RING_BASE = G::V_RING_BASE;
+    constexpr int NT = DH / 16;             // score steps per key block (16 of the head dimension each)
+    constexpr int NDB = DH / 32;            // 32-wide column blocks of the accumulators
+    constexpr int NG = 2 * NDB;             // value groups per key block: (half of the block's keys) x (column block)
     constexpr bool SPLIT = MODE == MODE_BF16_SPLIT;
     constexpr bool F16 = MODE == MODE_F16 || MODE == MODE_F16_ONLINE;   // fp16 weights and value operands
     constexpr bool PRESCAN = MODE == MODE_F16;                          // fixed reference from a key sample
@@ -341,10 +363,10 @@ __device__ __forceinline__ void attn_jvp_tile(
 
     // block x: K|tK in K-ring stage x & 3, V|tV in V-ring stage x & 3
     auto copy_k = [&](int blk) __attribute__((always_inline)) {
-        issue_pair_clamped<false, !ZT>(Kh, tKh, k_stride, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
+        issue_pair_clamped<DH, false, !ZT>(Kh, tKh, k_stride, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
     auto copy_v = [&](int blk) __attribute__((always_inline)) {
-        issue_pair_clamped<true, !ZT>(Vh, tVh, v_stride, blk * BC, Lkv,
+        issue_pair_clamped<DH, true, !ZT>(Vh, tVh, v_stride, blk * BC, Lkv,
                                       lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
     // Tile start.  One round trip to memory brings in K(0..3) (K ring, all four stages) and the tile's 128 rows of Q and
@@ -363,13 +385,13 @@ __device__ __forceinline__ void attn_jvp_tile(
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                const int rowblk = wave * 2 + i;
-                const int row = rowblk * 4 + (lane >> 4);
-                const int pc = lane & 15;
+            for (int i = 0; i < G::COPIES_PER_WAVE; ++i) {
+                const int rowblk = wave * G::COPIES_PER_WAVE + i;
+                const int row = rowblk * G::ROWS_PER_COPY + lane / G::LANES_PER_ROW;
+                const int pc = lane % G::LANES_PER_ROW;
                 int grow = tile_row0 + 32 * j + row;
                 grow = grow < Lq ? grow : Lq - 1;
-                const long goff = (long)grow * k_stride + ((pc ^ (row & 15)) << 4);
+                const long goff = (long)grow * k_stride + ((pc ^ G::k_swizzle(row)) << 4);
                 ATTN_JVP_LOAD_LDS(Qh + goff, lds0 + Q_STAGE + (uint32_t)j * TENSOR_BYTES + rowblk * 1024);
                 if constexpr (!PRIMAL) ATTN_JVP_LOAD_LDS(tQh + goff, lds0 + TQ_STAGE + (uint32_t)j * TENSOR_BYTES + rowblk * 1024);
             }
@@ -378,28 +400,32 @@ __device__ __forceinline__ void attn_jvp_tile(
 
     // per-lane LDS read addresses within stage 0 of the K ring / of the V ring; stage and tensor offsets are
     // 16-bit immediates of the read instructions
-    uint32_t kaddr0[8], vaddr0[4];
+    uint32_t kaddr0[NT], vaddr0[NDB];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) kaddr0[t] = lds0 + c * ROW_BYTES + (((2 * t + g) ^ (c & 15)) << 4);
+    for (int t = 0; t < NT; ++t) kaddr0[t] = lds0 + c * ROW_BYTES + (((2 * t + g) ^ G::k_swizzle(c)) << 4);
     {
+        // transposing read: the lane fetches 4 consecutive columns, 32 db + 16 hb + 4 (i & 3) .. +3, of key row
+        // 4 g + (i >> 2) (+ 8 for the second read of a fragment, + 16 for the block's second half); the row's 64-byte
+        // segments (32 columns) are swizzled by v_swizzle(row) >> 2, which those row offsets do not change
         const int i = lane & 15, hb = (lane >> 4) & 1;
-        const uint32_t rowpart = (4 * g + (i >> 2)) * ROW_BYTES + (2 * hb + ((i & 3) >> 1)) * 16 + 8 * (i & 1);
+        const int vrow = 4 * g + (i >> 2);
+        const uint32_t rowpart = vrow * ROW_BYTES + (2 * hb + ((i & 3) >> 1)) * 16 + 8 * (i & 1);
 #pragma unroll
-        for (int db = 0; db < 4; ++db) vaddr0[db] = lds0 + V_RING_BASE + rowpart + ((db ^ (i >> 2)) << 6);
+        for (int db = 0; db < NDB; ++db) vaddr0[db] = lds0 + V_RING_BASE + rowpart + ((db ^ (G::v_swizzle(vrow) >> 2)) << 6);
     }
 
     // Q^T / tQ^T as MFMA B operand: lane (c, g) holds row q0+c, elements 16t + 8g .. +7
-    bf16x8 qf[8], tqf[8];
+    bf16x8 qf[NT], tqf[NT];
     {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // K(0..3), Q and tQ are in
         __syncthreads();
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        for (int t = 0; t < NT; ++t) {
             qf[t] = lds_read_b128(kaddr0[t] + Q_STAGE + (uint32_t)wave * TENSOR_BYTES);
             if constexpr (!PRIMAL) tqf[t] = lds_read_b128(kaddr0[t] + TQ_STAGE + (uint32_t)wave * TENSOR_BYTES);
         }
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {   // keep them in accumulation registers: only MFMAs read them
+        for (int t = 0; t < NT; ++t) {   // keep them in accumulation registers: only MFMAs read them
             asm volatile("" : "+a"(qf[t]));
             if constexpr (!PRIMAL) asm volatile("" : "+a"(tqf[t]));
         }
@@ -407,9 +433,9 @@ __device__ __forceinline__ void attn_jvp_tile(
         if constexpr (!PRESCAN) start_v_ring();             // (the sampled-reference kernel first decides whether it takes the tile)
     }
 
-    f32x16 accO[4], accAB[4];
+    f32x16 accO[NDB], accAB[NDB];
 #pragma unroll
-    for (int db = 0; db < 4; ++db)
+    for (int db = 0; db < NDB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
 
@@ -577,7 +603,7 @@ __device__ __forceinline__ void attn_jvp_tile(
 #pragma unroll
         for (int e = 0; e < 16; ++e) { s[e] = 0.f; ts[e] = 0.f; }
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        for (int t = 0; t < NT; ++t) {
             const bf16x8 kf = lds_read_b128(kaddr0[t] + stage_off);
             s = MFMA(kf, qf[t], s);
             if constexpr (!PRIMAL) ts = MFMA(kf, tqf[t], ts);
@@ -610,7 +636,7 @@ __device__ __forceinline__ void attn_jvp_tile(
             bf16x8 hb8 = pb;
             if constexpr (!PRIMAL) hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
+            for (int db = 0; db < NDB; ++db) {
                 const uint32_t a = vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
                 const bf16x8 vf = join_tr(lds_read_tr_b64(a), lds_read_tr_b64(a + 8 * ROW_BYTES));
                 bf16x8 tvf = vf;   // placeholder when there is no tV
@@ -680,14 +706,14 @@ __device__ __forceinline__ void attn_jvp_tile(
         f32x16 s0, s1;
         auto scores_of_pair = [&](int i) __attribute__((always_inline)) {   // samples i and i+1 (or i twice)
             const uint32_t off0 = (uint32_t)i * KV_STAGE_BYTES, off1 = (uint32_t)(i + 1 < ns ? i + 1 : i) * KV_STAGE_BYTES;
-            bf16x8 ka[8], kb[8];
+            bf16x8 ka[NT], kb[NT];
 #pragma unroll
-            for (int t = 0; t < 8; ++t) { ka[t] = lds_read_b128(kaddr0[t] + off0); kb[t] = lds_read_b128(kaddr0[t] + off1); }
+            for (int t = 0; t < NT; ++t) { ka[t] = lds_read_b128(kaddr0[t] + off0); kb[t] = lds_read_b128(kaddr0[t] + off1); }
             FENCE();   // all sixteen reads in flight before the first MFMA waits for one
 #pragma unroll
             for (int e = 0; e < 16; ++e) { s0[e] = 0.f; s1[e] = 0.f; }
 #pragma unroll
-            for (int t = 0; t < 8; ++t) { s0 = MFMA(ka[t], qf[t], s0); s1 = MFMA(kb[t], qf[t], s1); }
+            for (int t = 0; t < NT; ++t) { s0 = MFMA(ka[t], qf[t], s0); s1 = MFMA(kb[t], qf[t], s1); }
             FENCE();
         };
         scores_of_pair(0);
@@ -758,8 +784,10 @@ __device__ __forceinline__ void attn_jvp_tile(
         static_for<4>([&](auto J) { softmax_pair(J, B0{}); });   // pairs 0-3 of block 0; pairs 4-7 follow in iteration 0
         // V(0) and V(1) have landed (the first iteration reads V(0) before its own barrier, and publishes V(1) with
         // it); the copies of V(2), issued last, may still be under way
-        if constexpr (ZT) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        // (a wave issues G::COPIES_PER_WAVE instructions per tensor block)
+        if constexpr (G::COPIES_PER_WAVE * (ZT ? 1 : 2) == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else if constexpr (G::COPIES_PER_WAVE * (ZT ? 1 : 2) == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(1)" ::: "memory");
         __syncthreads();
     }
 
@@ -810,7 +838,7 @@ __device__ __forceinline__ void attn_jvp_tile(
             // (the empty statements tie the accumulators to the accumulation registers on entry and exit, so that
             // the copies to and from arithmetic registers stay inside this block)
 #pragma unroll
-            for (int db = 0; db < 4; ++db) {
+            for (int db = 0; db < NDB; ++db) {
                 asm volatile("" : "+a"(accO[db]), "+a"(accAB[db]));
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
@@ -831,8 +859,9 @@ __device__ __forceinline__ void attn_jvp_tile(
     // next iteration during phase 2, the first VPRE value groups during phase 1, the rest KPRE steps / VPRE
     // groups ahead inside their own phase, through small register rings.
     constexpr int KPRE = 3, KRING = KPRE + 1, VPRE = 2, VRING = VPRE + 1;
-    constexpr int KFIRST = 2;   // value group after which the next iteration's first score fragments are requested
-    const LaneOffsets lofs = make_lane_offsets(wave, lane, k_stride, v_stride);
+    constexpr int KFIRST = NG == 8 ? 2 : 1;   // value group after which the next iteration's first score fragments are requested
+    static_assert(KPRE < NT && KFIRST + KPRE <= NG && VPRE < NG, "the fragment rings fit the key block's steps and groups");
+    const LaneOffsets lofs = make_lane_offsets<DH>(wave, lane, k_stride, v_stride);
     const int n_full = Lkv / BC;                       // blocks that need no row clamping
     bf16x8 kfr[KRING], tkfr[KRING], vfr[VRING], tvfr[VRING];
     auto read_k = [&](auto T, auto ST) __attribute__((always_inline)) {     // score step T of the block in K stage ST
@@ -843,9 +872,9 @@ __device__ __forceinline__ void attn_jvp_tile(
         if constexpr (!ZT) tkfr[t % KRING] = lds_read_b128(kaddr0[t] + off + TENSOR_BYTES);
         kfr[t % KRING] = lds_read_b128(kaddr0[t] + off);
     };
-    auto read_v = [&](auto G, auto ST) __attribute__((always_inline)) {     // value group G of the block in V stage ST
-        constexpr int gi = decltype(G)::value;
-        constexpr int t2 = gi >> 2, db = gi & 3;
+    auto read_v = [&](auto Gi, auto ST) __attribute__((always_inline)) {    // value group Gi of the block in V stage ST
+        constexpr int gi = decltype(Gi)::value;
+        constexpr int t2 = gi / NDB, db = gi % NDB;
         constexpr int off = decltype(ST)::value * KV_STAGE_BYTES + t2 * 16 * ROW_BYTES;
         if constexpr (!ZT)
             tvfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES),
@@ -854,26 +883,27 @@ __device__ __forceinline__ void attn_jvp_tile(
     };
 
     // The copies of iteration b: K(b+4) into K stage b & 3, V(b+3) into V stage (b+3) & 3, as 8 direct-to-LDS
-    // instructions per wave.  They are issued ONE per value group in phase 2, not back to back: the vector memory
+    // instructions per wave (4 at head dimension 64).  They are issued ONE per value group in phase 2, not back to back: the vector memory
     // pipe takes ~16 cycles per 1 KiB instruction and all four waves pass the barrier together, so a burst would
     // stall the in-order instruction stream behind the queue.
     auto issue_copy_piece = [&](auto FULLc, auto IDX, int b) __attribute__((always_inline)) {
         constexpr int idx = decltype(IDX)::value;
         constexpr int i = idx >> 2, which = idx & 3;      // row group of this wave; 0 K, 1 tK, 2 V, 3 tV
+        static_assert(i < G::COPIES_PER_WAVE, "one piece per value group covers exactly the iteration's copies");
         if constexpr (ZT && (which & 1)) return;          // no tangent tensors to copy
         const int blk = which < 2 ? b + 4 : b + 3;
         const char* base = which == 0 ? Kh : which == 1 ? tKh : which == 2 ? Vh : tVh;
         const uint32_t dst = lds0 + (which < 2 ? 0 : V_RING_BASE) + (uint32_t)(blk & 3) * KV_STAGE_BYTES +
-                             (which & 1) * TENSOR_BYTES + (wave * 2 + i) * 1024;
+                             (which & 1) * TENSOR_BYTES + (wave * G::COPIES_PER_WAVE + i) * 1024;
         if constexpr (decltype(FULLc)::value) {
             const uint32_t lo = which < 2 ? lofs.k[i] : lofs.v[i];
             load_lds_b128(base + (long)blk * (BC * (which < 2 ? k_stride : v_stride)), lo, __builtin_amdgcn_readfirstlane(dst));
         } else {
-            const int row = (wave * 2 + i) * 4 + (lane >> 4);
-            const int pc = lane & 15;
+            const int row = (wave * G::COPIES_PER_WAVE + i) * G::ROWS_PER_COPY + lane / G::LANES_PER_ROW;
+            const int pc = lane % G::LANES_PER_ROW;
             int grow = blk * BC + row;
             grow = grow < Lkv ? grow : Lkv - 1;
-            const int chunk = which < 2 ? (pc ^ (row & 15)) : (pc ^ ((row & 3) << 2));
+            const int chunk = pc ^ (which < 2 ? G::k_swizzle(row) : G::v_swizzle(row));
             ATTN_JVP_LOAD_LDS(base + (long)grow * (which < 2 ? k_stride : v_stride) + (chunk << 4), dst);
         }
     };
@@ -890,8 +920,10 @@ __device__ __forceinline__ void attn_jvp_tile(
         constexpr bool FULL = decltype(FULLc)::value;
         constexpr int PRODUCTS = PRIMAL ? 1 : ZT ? 2 : 3;         // matrix products per score step / per weight term
         constexpr int GROUP_MFMAS = SPLIT ? 2 * PRODUCTS : PRODUCTS;
-        using NS_P1 = std::integral_constant<int, 2 * PRODUCTS>;  // phase 1: two score steps per pair
-        using NS_P2 = std::integral_constant<int, GROUP_MFMAS>;   // phase 2: one value group per pair
+        constexpr int SPP = NT / 4;                                // phase 1: score steps per pair of score elements (2, or 1 at head dimension 64)
+        constexpr int PPG = 8 / NG;                                // phase 2: pairs per value group in each half of the groups (1, or 2)
+        using NS_P1 = std::integral_constant<int, SPP * PRODUCTS>;
+        using NS_P2 = std::integral_constant<int, GROUP_MFMAS>;
         using K1 = std::integral_constant<int, (U + 1) & 3>;    // K stage of block b+1
         using K2 = std::integral_constant<int, (U + 2) & 3>;    // K stage of block b+2
         using V0 = std::integral_constant<int, U>;              // V stage of block b
@@ -900,10 +932,10 @@ __device__ __forceinline__ void attn_jvp_tile(
         f32x16& s = SV(Bnext{});
         f32x16& ts = TSV(Bnext{});
         // ---- phase 1
-        static_for<8>([&](auto T) {
+        static_for<NT>([&](auto T) {
             constexpr int t = decltype(T)::value;
-            using J = std::integral_constant<int, 4 + t / 2>;
-            constexpr int s0 = (t % 2) * PRODUCTS;
+            using J = std::integral_constant<int, 4 + t / SPP>;
+            constexpr int s0 = (t % SPP) * PRODUCTS;
             if constexpr (t == 0) SMFMA0(kfr[t % KRING], qf[t], s); else SMFMA(kfr[t % KRING], qf[t], s);
             softmax_slot(J{}, std::integral_constant<int, s0>{}, NS_P1{}, Bcur{});
             FENCE();
@@ -917,33 +949,38 @@ __device__ __forceinline__ void attn_jvp_tile(
                 softmax_slot(J{}, std::integral_constant<int, s0 + 2>{}, NS_P1{}, Bcur{});
                 FENCE();
             }
-            if constexpr (t + KPRE < 8) read_k(std::integral_constant<int, t + KPRE>{}, K1{});
-            if constexpr (t >= 8 - VPRE) read_v(std::integral_constant<int, t - (8 - VPRE)>{}, V0{});
+            if constexpr (t + KPRE < NT) read_k(std::integral_constant<int, t + KPRE>{}, K1{});
+            if constexpr (t >= NT - VPRE) read_v(std::integral_constant<int, t - (NT - VPRE)>{}, V0{});
             FENCE();
         });
         // ---- middle
         SCORE_RESULTS_LAND();
         // all but the newest copies (8 instructions per wave and iteration, 4 without tangents) landed: K(b+2), V(b+1) are in
-        if constexpr (ZT) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        // (G::COPIES_PER_WAVE instructions per tensor block: 8 per iteration at head dimension 128, 4 at 64, half without tangents)
+        if constexpr (G::COPIES_PER_WAVE * (ZT ? 2 : 4) == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else if constexpr (G::COPIES_PER_WAVE * (ZT ? 2 : 4) == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
         // ... and visible to all waves after the barrier; all waves are done with K(b) and V(b-1).  A bare barrier:
         // the LDS reads still in flight (first value fragments of block b) read stages nobody overwrites yet.
         __builtin_amdgcn_s_barrier();
         FENCE();
         // ---- phase 2
-        static_for<8>([&](auto Gc) {
+        static_for<NG>([&](auto Gc) {
             constexpr int gi = decltype(Gc)::value;     // group = (t2, db)
-            constexpr int t2 = gi >> 2, db = gi & 3;
+            constexpr int t2 = gi / NDB, db = gi % NDB;
             const bf16x8 pb = as_bf16x8(wp[4 * t2], wp[4 * t2 + 1], wp[4 * t2 + 2], wp[4 * t2 + 3]);
             bf16x8 hb8 = pb;
             if constexpr (!PRIMAL) hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
             // vector work behind MFMA number `slot` of this group
             auto behind = [&](auto SLOT) __attribute__((always_inline)) {
                 constexpr int slot = decltype(SLOT)::value;
-                if constexpr (gi < 4) {
+                if constexpr (gi < NG / 2) {
                     // first touch of block b+1's scores (behind the second MFMA of a group where there is one: the
                     // score products' results have landed by then; the build's assembly check counts the wait states)
                     constexpr int first = GROUP_MFMAS >= 3 ? 1 : 0;
+                    // (head dimension 64: two pairs per group, the second one behind the next MFMA where there is one)
+                    if constexpr (PPG == 2 && GROUP_MFMAS >= first + 2 && slot == first + 1)
+                        softmax_part(std::integral_constant<int, 2 * gi + 1>{}, std::integral_constant<int, 0>{}, Bnext{});
                     if constexpr (slot == first) {
                         if constexpr (gi == 0) {
                             // (every lane of the new scores counts as read here, used or not: the score products of the
@@ -957,10 +994,19 @@ __device__ __forceinline__ void attn_jvp_tile(
                             }
                             if constexpr (ONLINE) online_check(Bnext{});
                         }
-                        softmax_part(std::integral_constant<int, gi>{}, std::integral_constant<int, 0>{}, Bnext{});
+                        softmax_part(std::integral_constant<int, PPG * gi>{}, std::integral_constant<int, 0>{}, Bnext{});
+                        if constexpr (PPG == 2 && GROUP_MFMAS < first + 2)
+                            softmax_part(std::integral_constant<int, 2 * gi + 1>{}, std::integral_constant<int, 0>{}, Bnext{});
                     }
+                } else if constexpr (PPG == 1) {
+                    softmax_late_slot(std::integral_constant<int, gi - NG / 2>{}, SLOT, NS_P2{}, Bnext{});
                 } else {
-                    softmax_late_slot(std::integral_constant<int, gi - 4>{}, SLOT, NS_P2{}, Bnext{});
+                    // two pairs per group: their eight late parts in order, dealt evenly over the group's MFMAs
+                    static_for<8>([&](auto Kc) {
+                        constexpr int k = decltype(Kc)::value;
+                        if constexpr (k * GROUP_MFMAS / 8 == slot)
+                            softmax_part(std::integral_constant<int, 2 * (gi - NG / 2) + k / 4>{}, std::integral_constant<int, 1 + k % 4>{}, Bnext{});
+                    });
                 }
             };
             accO[db] = VMFMA(vfr[gi % VRING], pb, accO[db]);
@@ -994,7 +1040,7 @@ __device__ __forceinline__ void attn_jvp_tile(
             }
             FENCE();
             issue_copy_piece(FULLc, Gc, b);
-            if constexpr (gi + VPRE < 8) read_v(std::integral_constant<int, gi + VPRE>{}, V0{});
+            if constexpr (gi + VPRE < NG) read_v(std::integral_constant<int, gi + VPRE>{}, V0{});
             if constexpr (gi >= KFIRST && gi < KFIRST + KPRE) read_k(std::integral_constant<int, gi - KFIRST>{}, K2{});
             FENCE();
         });
@@ -1049,7 +1095,7 @@ __device__ __forceinline__ void attn_jvp_tile(
         if constexpr (F16) {   // an fp16 weight that overflowed (inf) leaves inf or NaN in an accumulator
             float tot = 0.f;
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) tot += fabsf(accO[db][e]) + (PRIMAL ? 0.f : fabsf(accAB[db][e]));
             bad = bad || !(tot < 3.0e38f);
@@ -1073,7 +1119,7 @@ __device__ __forceinline__ void attn_jvp_tile(
             // Alg. 2 as printed: per block, running maximum, rescale of every accumulator, no overlap.
             // ctr follows the running value of rowsum(P o tS): B <- B - (ctr_new - ctr_old) O~ keeps it exact.
 #pragma unroll
-            for (int db = 0; db < 4; ++db)
+            for (int db = 0; db < NDB; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) { accO[db][e] = 0.f; accAB[db][e] = 0.f; }
             m = -INFINITY; l_part = 0.f; r_part = 0.f; l_part2 = 0.f; r_part2 = 0.f; ctr_h = 0.f; headroom = 0.f;
@@ -1107,7 +1153,7 @@ __device__ __forceinline__ void attn_jvp_tile(
                 r_part = fmaf(-delta, l_part, r_part);
                 const float da = delta * alpha;
 #pragma unroll
-                for (int db = 0; db < 4; ++db)
+                for (int db = 0; db < NDB; ++db)
 #pragma unroll
                     for (int e = 0; e < 16; ++e) {
                         if constexpr (!PRIMAL) accAB[db][e] = fmaf(accAB[db][e], alpha, -da * accO[db][e]);
@@ -1140,9 +1186,12 @@ __device__ __forceinline__ void attn_jvp_tile(
     // first copies (resident workgroups) off the staging areas of waves that are still reading.
     {
         typedef __attribute__((address_space(3))) f32x4 lds_float4;
-        const uint32_t stage_o = lds0 + (uint32_t)wave * 32768u, stage_t = stage_o + 16384u;
+        constexpr uint32_t OUT_ROW_BYTES = DH * 4;                 // a row of fp32 results
+        constexpr int OUT_CHUNKS = DH / 4;                         // ... in 16-byte chunks (32, or 16 at head dimension 64)
+        constexpr int ROWS_PER_STORE = 64 / OUT_CHUNKS;            // rows one store instruction covers (2, or 4)
+        const uint32_t stage_o = lds0 + (uint32_t)wave * (64u * OUT_ROW_BYTES), stage_t = stage_o + 32u * OUT_ROW_BYTES;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < NDB; ++db)
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4) {
                 float4 o4, t4;
@@ -1152,7 +1201,7 @@ __device__ __forceinline__ void attn_jvp_tile(
                 t4.y = (accAB[db][4 * v4 + 1] - mu * a1) * ft;
                 t4.z = (accAB[db][4 * v4 + 2] - mu * a2) * ft;
                 t4.w = (accAB[db][4 * v4 + 3] - mu * a3) * ft;
-                const uint32_t at = (uint32_t)c * 512u + (uint32_t)(((8 * db + 2 * v4 + g) ^ c) << 4);
+                const uint32_t at = (uint32_t)c * OUT_ROW_BYTES + (uint32_t)(((8 * db + 2 * v4 + g) ^ (c & (OUT_CHUNKS - 1))) << 4);
                 *reinterpret_cast<lds_float4*>((uintptr_t)(stage_o + at)) = f32x4{o4.x, o4.y, o4.z, o4.w};
                 if constexpr (!PRIMAL) *reinterpret_cast<lds_float4*>((uintptr_t)(stage_t + at)) = f32x4{t4.x, t4.y, t4.z, t4.w};
             }
@@ -1161,13 +1210,13 @@ __device__ __forceinline__ void attn_jvp_tile(
             LSE[bh * Lq + qrow] = ((m - headroom) + __builtin_amdgcn_logf(l_row * __builtin_amdgcn_exp2f(headroom))) * 0.6931471805599453f;
         const int o_row = out_blhd ? H * d_out : d_out;
         const long o_base = out_blhd ? (bidx * Lq * H + hidx) * d_out : bh * (long)Lq * d_out;
-        const int chunk = lane & 31;                 // 16-byte chunk of the row this lane stores: columns 4 chunk .. +3
+        const int chunk = lane % OUT_CHUNKS;         // 16-byte chunk of the row this lane stores: columns 4 chunk .. +3
         if (4 * chunk < d_out) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = 2 * i + g;             // row of the wave's 32
+            for (int i = 0; i < 32 / ROWS_PER_STORE; ++i) {
+                const int r = ROWS_PER_STORE * i + lane / OUT_CHUNKS;      // row of the wave's 32
                 const int row = q0 + r;
-                const uint32_t at = (uint32_t)r * 512u + (uint32_t)((chunk ^ r) << 4);
+                const uint32_t at = (uint32_t)r * OUT_ROW_BYTES + (uint32_t)((chunk ^ (r & (OUT_CHUNKS - 1))) << 4);
                 const f32x4 ov = *reinterpret_cast<const lds_float4*>((uintptr_t)(stage_o + at));
                 f32x4 tv_ = ov;
                 if constexpr (!PRIMAL) tv_ = *reinterpret_cast<const lds_float4*>((uintptr_t)(stage_t + at));
@@ -1196,7 +1245,7 @@ __device__ __forceinline__ void attn_jvp_tile(
 // behind them.  A tile ends with every wave past a workgroup barrier that follows its last LDS read, on every
 // path, so the next tile may start filling LDS at once.  Since gridDim.x is then a multiple of 8, tile w + k gridDim.x
 // runs on the same XCD as tile w, as the tile map in attn_jvp_tile assumes.
-template <int MODE, int TAN>
+template <int MODE, int TAN, int DH>
 __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
@@ -1215,7 +1264,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
         while (wall_clock64() - t0 < wait) __builtin_amdgcn_s_sleep(8);
     }
     for (int vw = blockIdx.x; vw < n_tiles; vw += gridDim.x)
-        attn_jvp_tile<MODE, TAN>(Q, K, V, tQ, tK, tV, O, tO, LSE, Lq, Lkv, scale, q_tiles, stats, wg_flags, H, blhd, out_bf16,
+        attn_jvp_tile<MODE, TAN, DH>(Q, K, V, tQ, tK, tV, O, tO, LSE, Lq, Lkv, scale, q_tiles, stats, wg_flags, H, blhd, out_bf16,
                                  d_out, out_blhd, online_min_blocks, lockstep_slots, vw, n_tiles);
 }
 
@@ -1224,46 +1273,48 @@ __global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
 // scale > 0: the kernel masks padded keys with a raw score of -inf and takes row maxima before scaling.
 // tk and tv are either both given or both absent (zero key/value tangents); single bf16 weights (FAST) are not built
 // for the latter.
-// Head dimensions 32, 64, 96: through zero-padded copies, which need the caller's workspace.
+// Head dimensions 128 and 64 are built natively; 32 and 96 run on zero-padded copies (to 128 columns), which need the
+// caller's workspace.
 static bool padded_head_dim(const Problem& p) {
-    return (p.d == 32 || p.d == 64 || p.d == 96) && p.workspace != nullptr &&
+    return (p.d == 32 || p.d == 96) && p.workspace != nullptr &&
            (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0 &&
            p.workspace_bytes >= pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv);
 }
 bool mfma_bf16_supports(const Problem& p) {
     const bool zt = p.tk == nullptr && p.tv == nullptr;     // (the API admits absent tangents only as tk+tv or tq+tk+tv)
-    return p.in_dtype == 0 && (p.d == D || padded_head_dim(p)) && p.scale > 0.f && !(zt && (p.flags & 1));
+    return p.in_dtype == 0 && (p.d == 128 || p.d == 64 || padded_head_dim(p)) && p.scale > 0.f && !(zt && (p.flags & 1));
 }
 
 // Dynamic-LDS limit of every instantiation a call may launch, raised once per device and before anything is enqueued.
+template <int DH>
 static hipError_t prepare_kernels(int dev) {
     const void* kernels[] = {
-        (const void*)attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL>,
-        (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_NONE>, (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_QUERY>,
-        (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_ALL>,
-        (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_NONE>, (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_QUERY>,
-        (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_ALL>,
-        (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_NONE>, (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_QUERY>,
-        (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_ALL>};
+        (const void*)attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL, DH>,
+        (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_NONE, DH>, (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_QUERY, DH>,
+        (const void*)attn_jvp_mfma_kernel<MODE_BF16_SPLIT, TAN_ALL, DH>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_NONE, DH>, (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_QUERY, DH>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16, TAN_ALL, DH>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_NONE, DH>, (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_QUERY, DH>,
+        (const void*)attn_jvp_mfma_kernel<MODE_F16_ONLINE, TAN_ALL, DH>};
     for (const void* k : kernels) {
-        const hipError_t e = ensure_dynamic_lds(k, LDS_BYTES, dev);
+        const hipError_t e = ensure_dynamic_lds(k, Geo<DH>::LDS_BYTES, dev);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
-hipError_t launch_mfma_bf16(const Problem& p_in) {
-    if (!mfma_bf16_supports(p_in)) return hipErrorInvalidValue;
+template <int DH>
+static hipError_t launch_dh(const Problem& p_in) {
     int dev = 0, cus = 0;
     {   // everything that can fail without a launch comes first: a failure here leaves nothing enqueued
         hipError_t e = device_cus(&dev, &cus);
-        if (e == hipSuccess) e = prepare_kernels(dev);
+        if (e == hipSuccess) e = prepare_kernels<DH>(dev);
         if (e != hipSuccess) return e;
         const long long tiles = (long long)((p_in.Lq + BR - 1) / BR) * p_in.B * p_in.H;
         if (tiles > 0x7fffffffLL) return hipErrorInvalidValue;
     }
     Problem p = p_in;
-    if (p_in.d != D) {      // run on zero-padded copies of the inputs; o, to keep the caller's width and layout
+    if (p_in.d != DH) {      // run on zero-padded copies of the inputs; o, to keep the caller's width and layout
         hipError_t e = launch_pad_inputs(p_in, &p);
         if (e != hipSuccess) return e;
     }
@@ -1278,7 +1329,7 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
         const bool res = resident && cus % 8 == 0 && blocks >= 2LL * cus && !(p.flags & 16);   // 16: ATTN_JVP_FLAG_NO_RESIDENT
         const long long grid = res ? cus : blocks;
         const int stagger = res ? STAGGER_TICKS : 0;
-        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTHREADS), LDS_BYTES, p.stream,
+        hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTHREADS), Geo<DH>::LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
                            p.o, p.to, p.lse, p.Lq, p.Lkv, p.scale, q_tiles, stats, wg_flags, p.H, p.layout, p.out_dtype,
@@ -1286,8 +1337,8 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
                            lockstep, (int)blocks, stagger);
         return hipGetLastError();
     };
-    // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the key sequence
-    // is long enough to amortise its per-call pre-pass and per-tile key sampling (measured break-even ~1500 keys)
+    // fp16 value path when the caller lent enough scratch (and did not ask for another variant) and the call is
+    // large enough to amortise its per-call pre-pass (see F16_MIN_KEYS)
     const bool f16 = !(p.flags & 3) && p.workspace != nullptr && (long long)p.B * p.H <= 65535 &&   // pre-pass grid.y
                      (p.Lkv >= F16_MIN_KEYS || (p.flags & 4) ||
                       (p.Lkv >= F16_MIN_KEYS_MANY_TILES && blocks >= (long long)F16_MANY_TILES_PER_CU * cus)) &&
@@ -1308,13 +1359,13 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
     auto run = [&](auto tan, const void* tv, const void* tv16) -> hipError_t {
         constexpr int T = decltype(tan)::value;
         resident = true;
-        if (!f16) return launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T>, p.v, tv, nullptr, nullptr);
-        hipError_t err = launch(attn_jvp_mfma_kernel<MODE_F16, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
+        if (!f16) return launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T, DH>, p.v, tv, nullptr, nullptr);
+        hipError_t err = launch(attn_jvp_mfma_kernel<MODE_F16, T, DH>, ws.v16, tv16, ws.stats, ws.wg_flags);
         resident = false;
         lockstep = ws.lockstep_slots;
-        if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_F16_ONLINE, T>, ws.v16, tv16, ws.stats, ws.wg_flags);
+        if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_F16_ONLINE, T, DH>, ws.v16, tv16, ws.stats, ws.wg_flags);
         lockstep = 0;
-        if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T>, p.v, tv, nullptr, ws.wg_flags);
+        if (err == hipSuccess) err = launch(attn_jvp_mfma_kernel<MODE_BF16_SPLIT, T, DH>, p.v, tv, nullptr, ws.wg_flags);
         return err;
     };
     if (p.tq == nullptr) {             // no tangents at all: plain attention forward
@@ -1323,11 +1374,16 @@ hipError_t launch_mfma_bf16(const Problem& p_in) {
         e = run(std::integral_constant<int, TAN_QUERY>{}, nullptr, nullptr);
     } else if (p.flags & 1) {
         resident = true;
-        e = launch(attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL>, p.v, p.tv, nullptr, nullptr);
+        e = launch(attn_jvp_mfma_kernel<MODE_BF16, TAN_ALL, DH>, p.v, p.tv, nullptr, nullptr);
     } else {
         e = run(std::integral_constant<int, TAN_ALL>{}, p.tv, ws.tv16);
     }
     return timer.finish(e);
+}
+
+hipError_t launch_mfma_bf16(const Problem& p) {
+    if (!mfma_bf16_supports(p)) return hipErrorInvalidValue;
+    return p.d == 64 ? launch_dh<64>(p) : launch_dh<128>(p);
 }
 
 }  // namespace attn_jvp

@@ -12,8 +12,8 @@
 namespace attn_jvp {
 namespace {
 
-constexpr int D = 128;
-constexpr int ROWS_PER_BLOCK = 1024;     // 256 threads: 16 lanes per row, 16 rows per pass, 64 passes
+constexpr int D = 128;                   // width of the zero-padded copies
+constexpr int ROWS_PER_BLOCK = 1024;     // rows of a tensor one block of the statistics kernel looks at
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -31,9 +31,10 @@ struct StatsArgs {
     int H, blhd;                  // layout of the tensors: [B,H,L,d] or [B,L,H,d]
 };
 
-// element offset of row `row` of head `bh` in a tensor with L rows per head
+// element offset of row `row` of head `bh` in a tensor with L rows of DH elements per head
+template <int DH>
 __device__ __forceinline__ long row_offset(long bh, int row, int L, int H, int blhd) {
-    return blhd ? (((bh / H) * L + row) * H + bh % H) * (long)D : (bh * L + row) * (long)D;
+    return blhd ? (((bh / H) * L + row) * H + bh % H) * (long)DH : (bh * L + row) * (long)DH;
 }
 
 constexpr int NORM_ROW_STEP = 16;   // row norms of Q, tQ, K, tK are taken from every 16th row (and the last one)
@@ -42,7 +43,11 @@ constexpr int NORM_ROW_STEP = 16;   // row norms of Q, tQ, K, tK are taken from 
 // Slot 0, 1: abs max of V, tV over every element; slots 2..5: largest squared row norm of Q, tQ, K, tK over the
 // sampled rows.  Every block writes its result (zero for an empty range or an absent tensor) to
 // partials[(head * gridDim.x + blockIdx.x) * 8 + tensor]: nothing needs clearing, and no two blocks share a word.
+// A row of DH bf16 is read by DH / 8 adjacent lanes (16 bytes each); 256 threads cover 16 rows per pass (32 at DH = 64).
+template <int DH>
 __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __restrict__ partials) {
+    constexpr int LPR = DH / 8;              // lanes per row
+    constexpr int RPP = 256 / LPR;           // rows per pass of the block
     const int which = blockIdx.z;
     const int L = a.L[which];
     const int row0 = blockIdx.x * ROWS_PER_BLOCK;
@@ -53,8 +58,8 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
         return;
     }
     const __hip_bfloat16* __restrict__ X = a.x[which];
-    const int sub = threadIdx.x & 15;            // 16 lanes x 16 B = one 256-byte row
-    const int r_in = threadIdx.x >> 4;
+    const int sub = threadIdx.x % LPR;
+    const int r_in = threadIdx.x / LPR;
     float best = 0.f;
     auto fold = [&](const uint4& w) {
         const uint32_t ws[4] = {w.x, w.y, w.z, w.w};
@@ -65,34 +70,36 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
         } else {
 #pragma unroll
             for (int i = 0; i < 4; ++i) { const float c = bf16_lo(ws[i]), e = bf16_hi(ws[i]); v = fmaf(c, c, fmaf(e, e, v)); }
-            // row norm^2: sum over the 16 lanes of the row
-            v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4); v += __shfl_xor(v, 8);
+            // row norm^2: sum over the lanes of the row
+            v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4);
+            if constexpr (LPR == 16) v += __shfl_xor(v, 8);
         }
         best = fmaxf(best, v);
     };
     if (which < 2) {
-        for (int rr = r_in; rr < ROWS_PER_BLOCK; rr += 64) {
+        for (int rr = r_in; rr < ROWS_PER_BLOCK; rr += 4 * RPP) {
             uint4 w[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {            // four independent 16-byte loads in flight per lane
-                const int row = row0 + rr + 16 * u;
-                w[u] = row < L ? ld16(X + row_offset(bh, row, L, a.H, a.blhd) + sub * 8) : make_uint4(0, 0, 0, 0);
+                const int row = row0 + rr + RPP * u;
+                w[u] = row < L ? ld16(X + row_offset<DH>(bh, row, L, a.H, a.blhd) + sub * 8) : make_uint4(0, 0, 0, 0);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) fold(w[u]);
         }
     } else {
-        // the block's 64 sampled rows (row0, row0 + 16, ...) in one round of four loads per lane, plus the tensor's
-        // last row, taken by the block whose range holds it
-        uint4 w[4];
+        // the block's 64 sampled rows (row0, row0 + 16, ...) in one round of loads, plus the tensor's last row, taken
+        // by the block whose range holds it
+        constexpr int NU = ROWS_PER_BLOCK / NORM_ROW_STEP / RPP;     // loads per lane: 4, or 2 at DH = 64
+        uint4 w[NU];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int row = row0 + NORM_ROW_STEP * (r_in + 16 * u);
-            w[u] = row < L ? ld16(X + row_offset(bh, row, L, a.H, a.blhd) + sub * 8) : make_uint4(0, 0, 0, 0);
+        for (int u = 0; u < NU; ++u) {
+            const int row = row0 + NORM_ROW_STEP * (r_in + RPP * u);
+            w[u] = row < L ? ld16(X + row_offset<DH>(bh, row, L, a.H, a.blhd) + sub * 8) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) fold(w[u]);
-        if (L - 1 >= row0 && L - 1 < row0 + ROWS_PER_BLOCK && r_in == 0) fold(ld16(X + row_offset(bh, L - 1, L, a.H, a.blhd) + sub * 8));
+        for (int u = 0; u < NU; ++u) fold(w[u]);
+        if (L - 1 >= row0 && L - 1 < row0 + ROWS_PER_BLOCK && r_in == 0) fold(ld16(X + row_offset<DH>(bh, L - 1, L, a.H, a.blhd) + sub * 8));
     }
 #pragma unroll
     for (int o = 1; o < 64; o <<= 1) best = fmaxf(best, __shfl_xor(best, o));
@@ -105,6 +112,7 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
 // Reduces the head's partial statistics (NaN in an input gives NaN here and ends in the bf16-pair fallback), leaves
 // them in stats[head * 8 ..] for the sweep kernels (block 0 of each head), clears the lock-step tickets (block 0 of
 // head 0), then converts its share of the head's V, tV rows.
+template <int DH>
 __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat16* __restrict__ V,
                                                              const __hip_bfloat16* __restrict__ tV,
                                                              const float* __restrict__ partials, int n_partials,
@@ -138,7 +146,7 @@ __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat1
     const long base = bh * elems_per_head;
     for (long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < elems_per_head; i += (long)gridDim.x * blockDim.x * 8) {
         // i indexes the head's rows in [L,d] order (the order of the fp16 copies); the source row may be strided
-        const long src = row_offset(bh, (int)(i / D), Lkv, H, blhd) + i % D;
+        const long src = row_offset<DH>(bh, (int)(i / DH), Lkv, H, blhd) + i % DH;
         const uint4 a = *reinterpret_cast<const uint4*>(V + src);
         const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
         __half2 ao[4];
@@ -261,13 +269,20 @@ hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out) {
     sa.H = p.H;
     sa.blhd = p.layout;
     auto bf = [](const void* x) { return static_cast<const __hip_bfloat16*>(x); };
-    hipLaunchKernelGGL(head_stats_kernel, dim3(l.n_partials, (unsigned)heads, 6), dim3(256), 0, p.stream, sa, partials);
+    if (p.d == 64)
+        hipLaunchKernelGGL(head_stats_kernel<64>, dim3(l.n_partials, (unsigned)heads, 6), dim3(256), 0, p.stream, sa, partials);
+    else
+        hipLaunchKernelGGL(head_stats_kernel<128>, dim3(l.n_partials, (unsigned)heads, 6), dim3(256), 0, p.stream, sa, partials);
     const long eph = (long)p.Lkv * p.d;
     int cx = (int)((eph / 8 + 255) / 256);
     if (cx > 512) cx = 512;
     if (cx < 1) cx = 1;
-    hipLaunchKernelGGL(convert_values_kernel, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), partials,
-                       l.n_partials, stats, tickets, V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
+    if (p.d == 64)
+        hipLaunchKernelGGL(convert_values_kernel<64>, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), partials,
+                           l.n_partials, stats, tickets, V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
+    else
+        hipLaunchKernelGGL(convert_values_kernel<128>, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), partials,
+                           l.n_partials, stats, tickets, V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
     out->stats = stats;
     out->wg_flags = wg_flags;
     out->v16 = V16;

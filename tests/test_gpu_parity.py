@@ -709,8 +709,8 @@ def test_mfma_bf16_outputs_are_the_rounded_fp32_outputs(variant):
 @pytest.mark.parametrize("case", ["f16", "bf16-pairs", "fast", "pairs-null-kv", "no-tangents", "blhd-bf16-out", "default-long"])
 @pytest.mark.parametrize("d", [32, 64, 96])
 def test_mfma_small_head_dims_through_zero_padded_copies(d, case):
-    """d in {32, 64, 96}: given a workspace the MFMA kernel runs on copies of the inputs padded with zero columns to
-    128 (the padding adds exact zeros to every product) and stores only the first d columns."""
+    """d = 64 is built natively; d in {32, 96}: given a workspace the MFMA kernel runs on copies of the inputs padded
+    with zero columns to 128 (the padding adds exact zeros to every product) and stores only the first d columns."""
     B, H, Lq, Lkv, flags, kw, null_kv, no_tan = 2, 2, 150, 333, 0, {}, False, False
     if case == "f16":
         flags = binding.FLAG_F16_ALWAYS
@@ -747,7 +747,14 @@ def test_mfma_small_head_dims_through_zero_padded_copies(d, case):
         return
     tol = FAST_TOL if case == "fast" else (2e-2, 3e-2, 1e-3) if case == "blhd-bf16-out" else None
     compare((back(o), back(to), lse.cpu().double().numpy()), ref, torch.bfloat16, f"d={d} {case}", tol=tol)
-    # without a workspace the MFMA kernel does not take this head dimension; AUTO then uses the vector kernel
+    if d == 64:
+        # built natively: no workspace needed (the weights then go in as bf16 pairs; same tolerance)
+        o2, to2, lse2 = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], tq, tk, tv, scale, kernel=binding.KERNEL_MFMA,
+                                                flags=flags & ~binding.FLAG_F16_ALWAYS, workspace=None, **kw)
+        torch.cuda.synchronize()
+        compare((back(o2), back(to2), lse2.cpu().double().numpy()), ref, torch.bfloat16, f"d={d} {case}, no workspace", tol=tol)
+        return
+    # without a workspace the MFMA kernel does not take these head dimensions; AUTO then uses the vector kernel
     with pytest.raises(binding.AttnJvpError):
         binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], tq, tk, tv, scale, kernel=binding.KERNEL_MFMA,
                                 flags=flags, workspace=None, **kw)
@@ -892,3 +899,48 @@ def test_f16_path_rows_of_different_spread_in_one_tile():
     t["q"] = q.to(torch.bfloat16)
     seen = _check_both_flag_settings(t, d ** -0.5, "video length, rows of std 1 and 6 in one tile", B, H, Lq)
     assert (seen["default"] == 3).all()
+
+
+# ------------------------------------------------------------------ head dimension 64, built natively
+
+@pytest.mark.parametrize("variant", ["bf16-pairs", "f16"])
+@pytest.mark.parametrize("Lq,Lkv", [(1, 1), (32, 64), (128, 65), (200, 333), (129, 127), (31, 1000), (517, 4), (384, 640),
+                                    (260, 4100)])
+def test_mfma_head_dim_64_shapes(Lq, Lkv, variant):
+    """The d = 64 instantiation of the sweep kernel (128-byte LDS rows, four score steps and four value groups per key
+    block) on ragged query tiles and key tails, one to 129 key blocks, against the oracle."""
+    t = random_inputs(6400 + Lq + Lkv, 2, 3, Lq, Lkv, 64, torch.bfloat16)
+    check_full(t, 64 ** -0.5, binding.KERNEL_MFMA, f"mfma d=64 {variant} Lq={Lq} Lkv={Lkv}", flags=VARIANTS[variant])
+
+
+def test_mfma_head_dim_64_every_key_length_up_to_five_blocks():
+    for Lkv in range(1, 161):
+        t = random_inputs(6500 + Lkv, 1, 1, 40, Lkv, 64, torch.bfloat16)
+        got = run_gpu(t, 64 ** -0.5, binding.KERNEL_MFMA, binding.FLAG_NO_F16)
+        ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], 64 ** -0.5)
+        e_o, e_to = rel_err(got[0], ref[0]), rel_err(got[1], ref[1])
+        assert e_o <= 1e-2 and e_to <= 2e-2 and np.abs(got[2] - ref[2]).max() <= 1e-3, f"Lkv={Lkv}: {e_o} {e_to}"
+
+
+@pytest.mark.parametrize("case", ["peaked-online", "null-kv", "no-tangents", "blhd", "long-default"])
+def test_mfma_head_dim_64_variants(case):
+    B, H, Lq, Lkv, d = 1, 2, 260, 2300, 64
+    gain = 8 ** 0.5 if case == "peaked-online" else 1.0
+    t = random_inputs(6600 + len(case), B, H, Lq, Lkv, d, torch.bfloat16, tangent_std=1.0, qk_gain=gain)
+    scale = d ** -0.5
+    kw, flags = {}, binding.FLAG_F16_ALWAYS if case == "peaked-online" else 0
+    if case in ("null-kv", "no-tangents"):
+        t["tk"].zero_(); t["tv"].zero_()
+    if case == "no-tangents":
+        t["tq"].zero_()
+    if case == "blhd":
+        kw = dict(layout=binding.LAYOUT_BLHD)
+    prep = (lambda x: x.permute(0, 2, 1, 3).contiguous()) if case == "blhd" else (lambda x: x)
+    dev = {n: prep(x.to(DEV)) for n, x in t.items()}
+    tq, tk, tv = {"null-kv": (dev["tq"], None, None), "no-tangents": (None, None, None)}.get(case, (dev["tq"], dev["tk"], dev["tv"]))
+    o, to, lse = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], tq, tk, tv, scale, kernel=binding.KERNEL_MFMA, flags=flags, **kw)
+    torch.cuda.synchronize()
+    ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], scale)
+    back = lambda x: prep(x).float().cpu().double().numpy()
+    got_to = back(to) if to is not None else ref[1]
+    compare((back(o), got_to, lse.cpu().double().numpy()), ref, torch.bfloat16, f"d=64 {case}")

@@ -61,7 +61,8 @@ def test_workspace_bytes(lib):
     assert n == 2 * 12 * 32760 * 128 * 2 + 512 + 12 * 256 * 4 + 512 + 12 * 32 * 32
     pad = (2 * 2 * 256 * 128 * 2) + 4 * (2 * 256 * 128 * 2)           # zero-padded q, tq and k, v, tk, tv
     f16 = 2 * 2 * 256 * 128 * 2 + 256 + 256 + 512 + 256               # fp16 copies + statistics + 4 tile flags + tickets + partials
-    assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 64) == pad + f16
+    assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 32) == pad + f16
+    assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 64) == 2 * 2 * 256 * 64 * 2 + 256 + 256 + 512 + 256   # built natively: no padded copies
     assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 48) == 0      # the MFMA kernel has no use for d = 48
     assert lib.attn_jvp_workspace_bytes(0, 2, 256, 256, 128) == 0
 
@@ -157,8 +158,8 @@ def test_argument_validation_returns_codes_without_launching(lib):
     assert _call(lib, opts=o) == 4
     o = AttnJvpOpts(); o.kernel = 2; o.in_dtype = 1        # MFMA kernels with fp32 inputs: d in {32, 64, 96, 128} only
     assert _call(lib, dims=(1, 1, 8, 8, 256), opts=o) == 3
-    o = AttnJvpOpts(); o.kernel = 2                        # MFMA kernel with d = 64
-    assert _call(lib, dims=(1, 1, 8, 8, 64), opts=o) == 3
+    o = AttnJvpOpts(); o.kernel = 2                        # MFMA kernel with d = 96 and no workspace for the padded copies
+    assert _call(lib, dims=(1, 1, 8, 8, 96), opts=o) == 3
     for bad_scale in (0.0, -0.125):                        # MFMA kernel needs scale > 0 (AUTO then takes the fp32 kernel)
         o = AttnJvpOpts(); o.kernel = 2
         assert _call(lib, scale=bad_scale, opts=o) == 3
