@@ -1246,7 +1246,7 @@ __device__ __forceinline__ void attn_jvp_tile(
 // path, so the next tile may start filling LDS at once.  Since gridDim.x is then a multiple of 8, tile w + k gridDim.x
 // runs on the same XCD as tile w, as the tile map in attn_jvp_tile assumes.
 template <int MODE, int TAN, int DH>
-__global__ __launch_bounds__(NTHREADS, 1) void attn_jvp_mfma_kernel(
+__global__ __launch_bounds__(NTHREADS, DH == 64 ? 2 : 1) void attn_jvp_mfma_kernel(
     const __hip_bfloat16* __restrict__ Q, const __hip_bfloat16* __restrict__ K, const void* __restrict__ V,
     const __hip_bfloat16* __restrict__ tQ, const __hip_bfloat16* __restrict__ tK, const void* __restrict__ tV,
     void* __restrict__ O, void* __restrict__ tO, float* __restrict__ LSE,
@@ -1326,8 +1326,9 @@ static hipError_t launch_dh(const Problem& p_in) {
     // tiles differ in length or return at once, keep one workgroup per tile, which the hardware balances.
     bool resident = false;
     auto launch = [&](auto kern, const void* v, const void* tv, const float* stats, int* wg_flags) -> hipError_t {
-        const bool res = resident && cus % 8 == 0 && blocks >= 2LL * cus && !(p.flags & 16);   // 16: ATTN_JVP_FLAG_NO_RESIDENT
-        const long long grid = res ? cus : blocks;
+        constexpr int WG_PER_CU = DH == 64 ? 2 : 1;       // what the kernel's registers and LDS allow
+        const bool res = resident && cus % 8 == 0 && blocks >= 2LL * WG_PER_CU * cus && !(p.flags & 16);   // 16: ATTN_JVP_FLAG_NO_RESIDENT
+        const long long grid = res ? (long long)WG_PER_CU * cus : blocks;
         const int stagger = res ? STAGGER_TICKS : 0;
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTHREADS), Geo<DH>::LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
