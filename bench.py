@@ -90,7 +90,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: video-DiT self-attention)")
+    ap.add_argument("--config", type=int, default=3, help="workload 1..5 (default 3: video-DiT self-attention); 6: the same shape at head dimension 64 (24 heads)")
     ap.add_argument("--variant", choices=["default", "bf16-pairs", "fast"], default="default",
                     help="MFMA kernel variant: default (workspace lent by the binding: fp16 value path from 2048 keys, or 256 with many query tiles, "
                          "on, bf16 pairs below), bf16-pairs (no workspace), fast (single bf16 weights; outside the "
@@ -188,6 +188,15 @@ def main():
     tflops = cfg.flops / (ms_per_step * 1e-3) / 1e12
     kern_tflops = cfg.flops / (kern_avg_ms * 1e-3) / 1e12
 
+    # Outside the timed region: the same K steps once more without the event pairs, whose records sit between the
+    # pre-pass and the sweep and cost short workloads a noticeable share of a step (nothing on the 15 ms headline)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step_plain = (time.perf_counter() - t0) * 1e3 / args.steps
+
     # Outside the timed region: the same workload through the two entry points that take no workspace from the caller.
     # attn_jvp_fwd (the plain 15-argument call) runs the hi + lo bf16-pair kernel; attn_jvp_fwd_static runs the same
     # kernels as the timed steps on the library's static scratch array (if the shape fits it).
@@ -243,6 +252,9 @@ def main():
         "config": {"workload": workload, "B": B, "H": H, "Lq": Lq, "Lkv": Lkv, "d": d,
                    "variant": args.variant, "kv_tangents": "null" if args.null_kv_tangents else "tensors", "layout": args.layout},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        # the same K steps without the HIP event pairs around the sweep kernel (not the headline: `value` is the timed region)
+        "ms_per_step_without_kernel_events": round(ms_per_step_plain, 4),
+        "tflops_without_kernel_events": round(cfg.flops / (ms_per_step_plain * 1e-3) / 1e12, 2),
         # counted: 12 Lq Lkv d per head (all six products); with tk = tv = NULL four of the six are executed
         "tflops_executed": round(tflops * (8.0 / 12.0 if args.null_kv_tangents else 1.0), 2),
         "roofline": {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": peak, "unit": "TFLOP/s",

@@ -80,16 +80,22 @@ extern "C" {
                                      lse stays [B, H, Lq]. */
 
 /* attn_jvp_opts.kernel */
-#define ATTN_JVP_KERNEL_AUTO 0    /* bf16, scale > 0 and d = 128 (or d in {32, 64, 96} with a workspace) -> bf16 MFMA kernel;
+#define ATTN_JVP_KERNEL_AUTO 0    /* bf16, scale > 0 and d in {64, 128} (or d in {32, 96} with a workspace) -> bf16 MFMA kernel;
                                      fp32 and d in {32, 64, 96, 128} -> fp32 MFMA kernel; everything else -> vector kernel */
 #define ATTN_JVP_KERNEL_FP32 1    /* fp32 vector-ALU streaming kernel: any dtype, d in {32, 64, 128, 256}, slow */
 #define ATTN_JVP_KERNEL_MFMA 2    /* matrix-core kernels.
-                                     bf16 inputs: scale > 0, d = 128; d in {32, 64, 96} given a workspace
-                                     of attn_jvp_workspace_bytes(...): the inputs are first copied there zero-padded to
-                                     128 columns (exact: the padding adds zeros to every product; half or more of the
-                                     matrix work is then spent on zeros).
+                                     bf16 inputs: scale > 0, d in {64, 128} (built natively); d in {32, 96} given a
+                                     workspace of attn_jvp_workspace_bytes(...): the inputs are first copied there
+                                     zero-padded to 128 columns (exact: the padding adds zeros to every product; a
+                                     quarter or more of the matrix work is then spent on zeros).
                                      fp32 inputs: d in {32, 64, 96, 128}, any finite scale, fp32 outputs; fp32 operands
-                                     and fp32 accumulation throughout (Alg. 2 as printed), no workspace, flags ignored */
+                                     and fp32 accumulation throughout (Alg. 2 as printed), no workspace, flags ignored.
+                                     Accuracy contract of this path: l, r and the accumulators are fp32 running sums
+                                     over the keys, so max |x - x_exact| / RMS(x) of o and to is within 1e-5 up to
+                                     256 keys and grows like sqrt(Lkv) beyond: within 1.5e-5 sqrt(Lkv / 256)
+                                     (measured on unit-variance scores: 5e-6 at 256 keys, 1.4e-5 at 4096); rows on
+                                     which one key carries the weight add up to 40 x 2^-24 x max|S| (the rounding of
+                                     the fp32 score itself, which the exponential turns into a relative error) */
 
 /* attn_jvp_opts.flags */
 #define ATTN_JVP_FLAG_FAST 1      /* EXPERIMENTAL, outside the accuracy contract (O within 1e-2, tO within 2e-2 of RMS): kept for
@@ -202,7 +208,7 @@ size_t attn_jvp_static_scratch_bytes(void);
  * Bytes of scratch the MFMA kernel can use for this shape (0 if it has no use for any).  d = 128: the fp16 value
  * path's 2 fp16 copies of [B,H,Lkv,d], 32 bytes of statistics per (batch, head), 4 bytes per 128-row query tile and
  * 32 bytes per (batch, head) and 1024 rows of the longer sequence, each part rounded up to 256 bytes, and 512 bytes
- * of counters.  d in {32, 64, 96}: in front of that, zero-padded [.,128] bf16 copies of the
+ * of counters (d = 64 likewise, with its own row width).  d in {32, 96}: in front of that, zero-padded [.,128] bf16 copies of the
  * six inputs (without them the MFMA kernel does not take these head dimensions).  Pure host arithmetic.
  */
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);

@@ -1,8 +1,11 @@
 // fp32 matrix-core streaming kernel for attention forward + JVP (paper App. C.1, Alg. 2) on gfx950.
 //
 // The path for fp32 inputs at head dims 32, 64, 96, 128: every product runs on v_mfma_f32_32x32x2_f32 (fp32
-// operands, fp32 accumulation), the softmax weights stay fp32 and nothing is rounded to a narrower type, so the
-// fp32 tolerance is met at matrix-core speed.  The algorithm is Alg. 2: row reference m, rescale factor
+// operands, fp32 accumulation), the softmax weights stay fp32 and nothing is rounded to a narrower type.  What is
+// left is the rounding of the fp32 running sums themselves (l, r and, foremost, the accumulators, which take one
+// rounded addition per two keys): measured max error 5e-6 of RMS at 256 keys, the size the 1e-5 tolerance for fp32
+// inputs is stated for, growing like sqrt(Lkv) beyond (1.4e-5 at 4096 keys); that growth law is part of the
+// interface's accuracy contract.  The algorithm is Alg. 2: row reference m, rescale factor
 // alpha = exp(m_old - m_new) applied to l, r and both accumulators, A and B summed into one accumulator (they are
 // only ever added), epilogue O/l, lse = m + log l, tO = (A + B - (r/l) O_unnorm)/l.  Two things differ from the
 // printed algorithm: the softmax scale, which it leaves out, multiplies S and tS; and m trails the running row

@@ -51,6 +51,9 @@ CONFIGS = {
     # logits scale*q.k have variance d*g^4/d = g^4; std 8 needs g = 8**0.5
     5: AttnJvpConfig(5, "video-14b-720p-stress-bf16", 1, 40, 75600, 75600, 128, "bf16",
                      math.sqrt(8.0), False, 1.0, False),
+    # not one of the five named configurations: the video self-attention shape at head dimension 64 with the same
+    # model width (24 heads of 64 instead of 12 of 128), for measuring the d = 64 instantiation of the kernels
+    6: AttnJvpConfig(6, "video-dit-self-d64-bf16", 1, 24, 32760, 32760, 64, "bf16", 1.0, False, 0.5, False),
 }
 
 _TENSORS = ("q", "k", "v", "tq", "tk", "tv")
