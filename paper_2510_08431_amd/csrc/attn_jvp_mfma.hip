@@ -1,4 +1,4 @@
-// bf16 matrix-core (MFMA) streaming kernel for attention forward + JVP (paper Alg. 2), d = 128.
+// bf16 matrix-core (MFMA) streaming kernel for attention forward + JVP (paper Alg. 2), head dimension 128 or 64.
 //
 // One workgroup = 4 wavefronts = 128 query rows; each wavefront owns 32 query rows for the whole
 // key/value sweep.  All contractions of Alg. 2's inner loop run on v_mfma_f32_32x32x16_bf16 in the
