@@ -85,6 +85,49 @@ def bench_rmsnorm(args, cfg, dev):
     print(json.dumps(out))
 
 
+def sustained_mfma_rates(torch, binding, dev, iters=150000, with_gemm=False):
+    """What the chip at hand sustains on back-to-back dense 8-pass MFMAs (the library's rate probe: one wave per SIMD
+    on every compute unit, nothing else in the loop), by operand VALUES: all-zero operands run at the full clock,
+    N(0,1) operands at the clock the power limit leaves.  TFLOP/s each; optionally the same comparison on a library
+    GEMM (torch.matmul, 8192^3)."""
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    out = torch.empty(256 * cus, dtype=torch.float32, device=dev)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(4242)
+    vals = torch.randn(8 * 256 * 8, generator=g)
+    ops = {"bf16_zero_operands": (torch.zeros(8 * 256 * 8, dtype=torch.bfloat16), 0),
+           "bf16_normal_operands": (vals.to(torch.bfloat16), 0),
+           "fp16_normal_operands": (vals.to(torch.float16), 1)}
+    res = {}
+    for name, (x, f16) in ops.items():
+        x = x.to(dev)
+        binding.attn_jvp_mfma_rate_probe(x, out, f16, 2000)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        flops = binding.attn_jvp_mfma_rate_probe(x, out, f16, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        res[name + "_tflops"] = round(flops / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    if with_gemm:
+        n = 8192
+        for dt, nm in ((torch.bfloat16, "bf16"), (torch.float16, "fp16")):
+            for kind in ("zero", "normal"):
+                a = torch.zeros(n, n, device=dev, dtype=dt) if kind == "zero" else torch.randn(n, n, device=dev).to(dt)
+                b = a if kind == "zero" else torch.randn(n, n, device=dev).to(dt)
+                for _ in range(5):
+                    a @ b
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(60):
+                    a @ b
+                e1.record()
+                torch.cuda.synchronize()
+                res[f"library_gemm_8192_{nm}_{kind}_operands_tflops"] = round(2.0 * n ** 3 * 60 / (e0.elapsed_time(e1) * 1e-3) / 1e12, 1)
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +153,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain 1 GiB device-to-device copy (known traffic) for scaling HBM counters")
+    ap.add_argument("--mfma-calibration", action="store_true",
+                    help="run only the sustained-MFMA-rate measurement (the library's rate probe with all-zero and N(0,1) "
+                         "operands, and a library GEMM on the same two kinds of data) and print it as one JSON line")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "hbm_traffic.json"),
                     help="optional file with measured HBM bytes per launch, {workload: bytes}")
     args = ap.parse_args()
@@ -138,6 +184,10 @@ def main():
     cfg = CONFIGS[args.config]
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.mfma_calibration:
+        print(json.dumps({"mfma_sustained": sustained_mfma_rates(torch, binding, dev, iters=400000, with_gemm=True),
+                          "published_peak_tflops": PEAK_BF16_TFLOPS}))
+        return
     if args.op == "rmsnorm":
         bench_rmsnorm(args, cfg, dev)
         return
@@ -266,6 +316,16 @@ def main():
 
     if other_entries:
         out["entry_points_without_caller_workspace"] = other_entries
+    if not f32 and kernel_name == "attn_jvp_mfma_kernel":
+        # Outside the timed region: the rate this chip sustains on nothing but dense MFMAs, by operand values.  `frac`
+        # above stays against the published peak; this says how much of that peak is reachable on real data here.
+        sus = sustained_mfma_rates(torch, binding, dev)
+        fp16_path = arithmetic.startswith("bf16 in, bf16 score MFMA + fp16")
+        ref = (2.0 / (1.0 / sus["bf16_normal_operands_tflops"] + 1.0 / sus["fp16_normal_operands_tflops"])
+               if fp16_path else sus["bf16_normal_operands_tflops"])     # half the products of the fp16 path are fp16 MFMAs
+        sus["same_mix_of_mfma_types_tflops"] = round(ref, 1)
+        out["mfma_sustained"] = sus
+        out["roofline"]["frac_of_sustained_mfma_rate"] = round(kern_tflops / ref, 4)
 
     if not args.no_cpu_baseline:
         # the fp64 oracle, as it stands, on a bounded sample of the same workload: a seeded set of query rows

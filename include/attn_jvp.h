@@ -229,6 +229,22 @@ size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 int attn_jvp_rmsnorm_fwd(const void* x, const void* tx, const float* w, void* y, void* ty,
                          long long rows, int d, float eps, int dtype, void* stream);
 
+/* Measurement aid (no passage of the paper: it prices the kernels above).  Runs `iters` x 16 back-to-back
+ * v_mfma_f32_32x32x16_bf16 (f16 = 0) or _f16 (f16 != 0) instructions per wavefront, one wavefront per SIMD on every
+ * compute unit, on the operand VALUES the caller supplies, asynchronously on `stream`; the caller times it (events on
+ * that stream).  The rate a chip sustains on dense matrix instructions depends on those values: all-zero operands run
+ * at the full clock, random ones at the clock the power limit leaves.
+ *   operands  device, 8 x 256 x 16 bytes (eight sets of one 16-byte fragment per lane: four A and four B operands,
+ *             bf16 or fp16 bit patterns), 16-byte aligned, read only;
+ *   out       device, 256 floats per compute unit (sums of the accumulators, so that the work is observable);
+ *   iters     1 .. ATTN_JVP_RATE_PROBE_MAX_ITERS (bounds the run time to about a second);
+ *   mfmas_per_wave, waves   host, optional: instructions each wavefront issues, and how many wavefronts run;
+ *             flops = 32768 x mfmas_per_wave x waves.
+ * Errors as above (NULL_PTR, BAD_SHAPE, MISALIGNED from host checks; LAUNCH_FAILED). */
+#define ATTN_JVP_RATE_PROBE_MAX_ITERS 2000000
+int attn_jvp_mfma_rate_probe(const void* operands, float* out, int f16, int iters, void* stream,
+                             long long* mfmas_per_wave, int* waves);
+
 /* Static, NUL-terminated description of an error code (never NULL). */
 const char* attn_jvp_strerror(int code);
 

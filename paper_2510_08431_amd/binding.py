@@ -64,6 +64,8 @@ def load_library():
     lib.attn_jvp_version.restype = ci
     lib.attn_jvp_rmsnorm_fwd.argtypes = [vp] * 5 + [ctypes.c_longlong, ci, ctypes.c_float, ci, vp]
     lib.attn_jvp_rmsnorm_fwd.restype = ci
+    lib.attn_jvp_mfma_rate_probe.argtypes = [vp, vp, ci, ci, vp, ctypes.POINTER(ctypes.c_longlong), ctypes.POINTER(ci)]
+    lib.attn_jvp_mfma_rate_probe.restype = ci
     lib.attn_jvp_workspace_bytes.argtypes = [ci] * 5
     lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
     _lib = lib
@@ -238,6 +240,31 @@ def attn_jvp_rmsnorm_fwd(x, tx, w, eps, out=None, stream=None):
     if rc != 0:
         raise AttnJvpError(rc, attn_jvp_strerror(rc))
     return y, ty
+
+
+def attn_jvp_mfma_rate_probe(operands, out, f16, iters, stream=None):
+    """Enqueue the library's back-to-back MFMA loop on the operand values given (measurement aid).
+
+    operands: uint8/int tensor of 8 * 256 * 16 bytes on the GPU (bf16 or fp16 bit patterns); out: float32 tensor with
+    at least 256 elements per compute unit.  Returns the number of floating-point operations the launch performs;
+    the caller times it."""
+    lib = load_library()
+    if not (operands.is_cuda and out.is_cuda and operands.is_contiguous() and out.is_contiguous()):
+        raise ValueError("operands and out must be contiguous GPU tensors")
+    if operands.numel() * operands.element_size() < 8 * 256 * 16:
+        raise ValueError("operands must hold 8 x 256 x 16 bytes")
+    cus = torch.cuda.get_device_properties(out.device).multi_processor_count
+    if out.dtype != torch.float32 or out.numel() < 256 * cus:
+        raise ValueError("out must be float32 with 256 elements per compute unit")
+    if stream is None:
+        stream = torch.cuda.current_stream(out.device)
+    per_wave, waves = ctypes.c_longlong(0), ctypes.c_int(0)
+    with torch.cuda.device(out.device):
+        rc = lib.attn_jvp_mfma_rate_probe(operands.data_ptr(), out.data_ptr(), int(bool(f16)), int(iters),
+                                          stream.cuda_stream, ctypes.byref(per_wave), ctypes.byref(waves))
+    if rc != 0:
+        raise AttnJvpError(rc, attn_jvp_strerror(rc))
+    return 32768.0 * per_wave.value * waves.value
 
 
 def attn_jvp_fwd(q, k, v, tq, tk, tv, scale, out=None):

@@ -171,6 +171,15 @@ int attn_jvp_rmsnorm_fwd(const void* x, const void* tx, const float* w, void* y,
     return attn_jvp::launch_rmsnorm_jvp(p) == hipSuccess ? ATTN_JVP_OK : ATTN_JVP_LAUNCH_FAILED;
 }
 
+int attn_jvp_mfma_rate_probe(const void* operands, float* out, int f16, int iters, void* stream,
+                             long long* mfmas_per_wave, int* waves) {
+    if (!operands || !out) return ATTN_JVP_NULL_PTR;
+    if (iters <= 0 || iters > ATTN_JVP_RATE_PROBE_MAX_ITERS) return ATTN_JVP_BAD_SHAPE;
+    if (!aligned16(operands) || !aligned16(out)) return ATTN_JVP_MISALIGNED;
+    return attn_jvp::launch_mfma_rate_probe(operands, out, f16 != 0, iters, static_cast<hipStream_t>(stream),
+                                            mfmas_per_wave, waves) == hipSuccess ? ATTN_JVP_OK : ATTN_JVP_LAUNCH_FAILED;
+}
+
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
     if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0) return 0;
     if (d != 128 && d != 32 && d != 64 && d != 96) return 0;

@@ -77,6 +77,12 @@ size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv);
 hipError_t launch_pad_inputs(const Problem& p, Problem* padded);
 hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out);
 
+// Measurement aid: back-to-back MFMAs on every compute unit with the caller's operand values (mfma_rate_probe.hip).
+// operands: 8 x 256 x 16 bytes; out: 256 floats per compute unit.  Reports how many MFMAs a wave issues and how many
+// waves run, so that the caller can turn a measured time into a rate.
+hipError_t launch_mfma_rate_probe(const void* operands, float* out, int f16, int iters, hipStream_t stream,
+                                  long long* mfmas_per_wave, int* waves);
+
 // RMS normalisation with gain + JVP over `rows` rows of length d
 struct RmsNormProblem {
     const void *x, *tx;

@@ -12,7 +12,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 BUILD = os.path.join(ROOT, "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-OTHER_SOURCES = ("attn_jvp_fp32", "attn_jvp_mfma", "attn_jvp_mfma_f32", "attn_jvp_prepass", "rmsnorm_jvp")
+CSRC = os.path.join(ROOT, "paper_2510_08431_amd", "csrc")
+OTHER_SOURCES = tuple(sorted(f[:-4] for f in os.listdir(CSRC) if f.endswith(".hip") and f != "attn_jvp_api.hip"))
 
 CHILD = r"""
 import ctypes, sys
@@ -23,6 +24,7 @@ lib = binding.load_library()
 import tests.test_library_abi as t
 t.test_argument_validation_returns_codes_without_launching(lib)
 t.test_rmsnorm_argument_validation_returns_codes_without_launching(lib)
+t.test_rate_probe_argument_validation_returns_codes_without_launching(lib)
 t.test_static_entry_point_rejects_on_the_host(lib)
 t.test_version_and_strerror(lib)
 t.test_workspace_bytes(lib)

@@ -28,7 +28,7 @@ def declared_functions():
 def test_header_symbols_exported(lib):
     names = declared_functions()
     assert {"attn_jvp_fwd", "attn_jvp_fwd_ex", "attn_jvp_fwd_static", "attn_jvp_static_scratch_bytes", "attn_jvp_rmsnorm_fwd",
-            "attn_jvp_strerror", "attn_jvp_version", "attn_jvp_workspace_bytes"} <= set(names)
+            "attn_jvp_mfma_rate_probe", "attn_jvp_strerror", "attn_jvp_version", "attn_jvp_workspace_bytes"} <= set(names)
     for n in names:
         assert hasattr(lib, n), f"{n} declared in the header but not exported"
 
@@ -179,6 +179,19 @@ def test_rmsnorm_argument_validation_returns_codes_without_launching(lib):
         assert call(p) == 4
     assert call(rows=0) == 2 and call(d=0) == 2 and call(eps=-1.0) == 2 and call(eps=float("nan")) == 2
     assert call(d=96) == 3 and call(dtype=5) == 3
+
+
+def test_rate_probe_argument_validation_returns_codes_without_launching(lib):
+    """The measurement aid checks its arguments on the host like the other entry points (no GPU needed)."""
+    import ctypes
+    fn = lib.attn_jvp_mfma_rate_probe
+    ok = 0x10000
+    assert fn(None, ok, 0, 10, None, None, None) == 1
+    assert fn(ok, None, 0, 10, None, None, None) == 1
+    assert fn(ok, ok, 0, 0, None, None, None) == 2
+    assert fn(ok, ok, 1, 2_000_001, None, None, None) == 2
+    assert fn(ok + 4, ok, 0, 10, None, None, None) == 4
+    assert fn(ok, ok + 8, 0, 10, None, None, None) == 4
 
 
 def test_binding_rejects_cpu_tensors_and_bad_shapes():
