@@ -206,7 +206,7 @@ size_t attn_jvp_static_scratch_bytes(void);
 
 /*
  * Bytes of scratch the MFMA kernel can use for this shape (0 if it has no use for any).  d = 128: the fp16 value
- * path's 2 fp16 copies of [B,H,Lkv,d], 32 bytes of statistics per (batch, head), 4 bytes per 128-row query tile and
+ * path's 2 fp16 copies of V and tV (Lkv rounded up to a multiple of 32 keys: they are kept as whole 32-key blocks), 32 bytes of statistics per (batch, head), 4 bytes per 128-row query tile and
  * 32 bytes per (batch, head) and 1024 rows of the longer sequence, each part rounded up to 256 bytes, and 512 bytes
  * of counters (d = 64 likewise, with its own row width).  d in {32, 96}: in front of that, zero-padded [.,128] bf16 copies of the
  * six inputs (without them the MFMA kernel does not take these head dimensions).  Pure host arithmetic.

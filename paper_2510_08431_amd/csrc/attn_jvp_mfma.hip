@@ -217,10 +217,37 @@ __device__ __forceinline__ void issue_pair_clamped(const char* Xh, const char* t
         if constexpr (WITH_TANGENT) ATTN_JVP_LOAD_LDS(tXh + goff, dst + G::TENSOR_BYTES);
     }
 }
+// The fp16 copies of V and tV that the pre-pass leaves in the workspace are stored TRANSPOSED, key block by key block:
+// block j of a head is [DH][32] fp16 (64-byte rows, one per column of V; 32 * DH * 2 bytes = TENSOR_BYTES, the last
+// block zero-filled past Lkv), and inside a row the 32 keys stand in the order in which the score MFMAs leave them in
+// a lane's result registers: position 16 t2 + 8 g + t holds key 16 t2 + 4 g + (t & 3) + 8 (t >> 2).  The A operand of
+// a value MFMA (32 columns of V x 16 keys; lane (c, g) feeds column c, contraction indices 8 g .. 8 g + 7) is then ONE
+// 16-byte read, chunk 2 t2 + g of row c, where the row-major bf16 blocks need two transposing 8-byte reads.  A stage
+// holds the block as it is in memory, except that 16-byte chunk q of row r sits at chunk q ^ ((r >> 2) & 3): the 16
+// lanes that a 128-bit read serves together (consecutive c) then cover all 64 banks.  As with the other copies the
+// swizzle is applied on the global side; the byte offset of a lane inside a 1-KiB piece (16 rows) is fixed.
+__device__ __forceinline__ uint32_t v16t_lane_offset(int lane) {
+    return (uint32_t)(lane >> 2) * 64 + (uint32_t)(((lane & 3) ^ ((lane >> 4) & 3)) << 4);
+}
+template <int DH, bool WITH_TANGENT>
+__device__ __forceinline__ void issue_pair_v16t(const char* Xh, const char* tXh, int blk, int n_blocks, uint32_t stage_base,
+                                                int wave, int lane) {
+    using G = Geo<DH>;
+    const int b = blk < n_blocks ? blk : n_blocks - 1;      // past the end: any finite data (the weights there are zero)
+    const uint32_t lo = v16t_lane_offset(lane);
+#pragma unroll
+    for (int i = 0; i < G::COPIES_PER_WAVE; ++i) {
+        const int piece = wave * G::COPIES_PER_WAVE + i;
+        const long goff = (long)b * G::TENSOR_BYTES + piece * 1024 + lo;
+        const uint32_t dst = stage_base + piece * 1024;
+        ATTN_JVP_LOAD_LDS(Xh + goff, dst);
+        if constexpr (WITH_TANGENT) ATTN_JVP_LOAD_LDS(tXh + goff, dst + G::TENSOR_BYTES);
+    }
+}
 // Same copy for a block known to lie entirely inside the sequence: the per-lane byte offsets (row and swizzled
 // chunk) never change, so they are computed once and only the uniform block base advances.
 struct LaneOffsets { uint32_t k[2], v[2]; };
-template <int DH>
+template <int DH, bool V16T>
 __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int k_stride, int v_stride) {
     using G = Geo<DH>;
     LaneOffsets o = {};
@@ -229,7 +256,8 @@ __device__ __forceinline__ LaneOffsets make_lane_offsets(int wave, int lane, int
         const int row = (wave * G::COPIES_PER_WAVE + i) * G::ROWS_PER_COPY + lane / G::LANES_PER_ROW;
         const int pc = lane % G::LANES_PER_ROW;
         o.k[i] = row * k_stride + ((pc ^ G::k_swizzle(row)) << 4);
-        o.v[i] = row * v_stride + ((pc ^ G::v_swizzle(row)) << 4);
+        o.v[i] = V16T ? (wave * G::COPIES_PER_WAVE + i) * 1024 + v16t_lane_offset(lane)
+                      : row * v_stride + ((pc ^ G::v_swizzle(row)) << 4);
     }
     return o;
 }
@@ -353,21 +381,22 @@ __device__ __forceinline__ void attn_jvp_tile(
     const long q_base = blhd ? (bidx * Lq * H + hidx) * D : bh * (long)Lq * D;
     const long kv_base = blhd ? (bidx * Lkv * H + hidx) * D : bh * (long)Lkv * D;
     const int k_stride = row_elems * 2;                                  // bytes between key rows
-    const int v_stride = F16 ? ROW_BYTES : k_stride;
-    const long v_base = F16 ? bh * (long)Lkv * D : kv_base;
+    const int n_blocks = (Lkv + BC - 1) / BC;
+    const int v_stride = F16 ? ROW_BYTES : k_stride;                     // (fp16 copies: whole transposed blocks, see issue_pair_v16t)
+    const long v_base = F16 ? bh * (long)n_blocks * (BC * D) : kv_base;
     const char* Kh = reinterpret_cast<const char*>(K) + kv_base * 2;
     const char* tKh = reinterpret_cast<const char*>(tK) + kv_base * 2;
     const char* Vh = static_cast<const char*>(V) + v_base * 2;           // bf16, or the fp16 copies
     const char* tVh = static_cast<const char*>(tV) + v_base * 2;
-    const int n_blocks = (Lkv + BC - 1) / BC;
 
     // block x: K|tK in K-ring stage x & 3, V|tV in V-ring stage x & 3
     auto copy_k = [&](int blk) __attribute__((always_inline)) {
         issue_pair_clamped<DH, false, !ZT>(Kh, tKh, k_stride, blk * BC, Lkv, lds0 + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
     };
     auto copy_v = [&](int blk) __attribute__((always_inline)) {
-        issue_pair_clamped<DH, true, !ZT>(Vh, tVh, v_stride, blk * BC, Lkv,
-                                      lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES, wave, lane);
+        const uint32_t stage = lds0 + V_RING_BASE + (uint32_t)(blk & 3) * KV_STAGE_BYTES;
+        if constexpr (F16) issue_pair_v16t<DH, !ZT>(Vh, tVh, blk, n_blocks, stage, wave, lane);
+        else issue_pair_clamped<DH, true, !ZT>(Vh, tVh, v_stride, blk * BC, Lkv, stage, wave, lane);
     };
     // Tile start.  One round trip to memory brings in K(0..3) (K ring, all four stages) and the tile's 128 rows of Q and
     // tQ, which are staged through the V ring's area (64 KiB, not needed yet) so that they, too, come as whole
@@ -400,10 +429,14 @@ __device__ __forceinline__ void attn_jvp_tile(
 
     // per-lane LDS read addresses within stage 0 of the K ring / of the V ring; stage and tensor offsets are
     // 16-bit immediates of the read instructions
-    uint32_t kaddr0[NT], vaddr0[NDB];
+    uint32_t kaddr0[NT], vaddr0[F16 ? 2 : NDB];
 #pragma unroll
     for (int t = 0; t < NT; ++t) kaddr0[t] = lds0 + c * ROW_BYTES + (((2 * t + g) ^ G::k_swizzle(c)) << 4);
-    {
+    if constexpr (F16) {
+        // transposed fp16 blocks: chunk 2 t2 + g of row c (of column block db: + 32 db rows, an immediate), swizzled
+#pragma unroll
+        for (int t2 = 0; t2 < 2; ++t2) vaddr0[t2] = lds0 + V_RING_BASE + c * 64 + (((2 * t2 + g) ^ ((c >> 2) & 3)) << 4);
+    } else {
         // transposing read: the lane fetches 4 consecutive columns, 32 db + 16 hb + 4 (i & 3) .. +3, of key row
         // 4 g + (i >> 2) (+ 8 for the second read of a fragment, + 16 for the block's second half); the row's 64-byte
         // segments (32 columns) are swizzled by v_swizzle(row) >> 2, which those row offsets do not change
@@ -629,6 +662,12 @@ __device__ __forceinline__ void attn_jvp_tile(
         const float u0 = max3(t0, t1, t2_), u1 = max3(t3, t4, sv[15]);
         return xhalf_max(max3(u0, u1, u1)) * c2;
     };
+    // A operand of a value MFMA (32 columns of V x 16 keys): one 128-bit read of a transposed fp16 block, or two
+    // transposing 64-bit reads of a row-major bf16 block (rows 8 apart)
+    auto read_v_fragment = [&](uint32_t a) __attribute__((always_inline)) -> bf16x8 {
+        if constexpr (F16) return lds_read_b128(a);
+        else return join_tr(lds_read_tr_b64(a), lds_read_tr_b64(a + 8 * ROW_BYTES));
+    };
     auto plain_values = [&](uint32_t stage_off) __attribute__((always_inline)) {   // unscheduled: safe sweep
 #pragma unroll
         for (int t2 = 0; t2 < 2; ++t2) {
@@ -637,11 +676,10 @@ __device__ __forceinline__ void attn_jvp_tile(
             if constexpr (!PRIMAL) hb8 = as_bf16x8(wh[4 * t2], wh[4 * t2 + 1], wh[4 * t2 + 2], wh[4 * t2 + 3]);
 #pragma unroll
             for (int db = 0; db < NDB; ++db) {
-                const uint32_t a = vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
-                const bf16x8 vf = join_tr(lds_read_tr_b64(a), lds_read_tr_b64(a + 8 * ROW_BYTES));
+                const uint32_t a = F16 ? vaddr0[t2] + stage_off + db * (32 * 64) : vaddr0[db] + stage_off + t2 * 16 * ROW_BYTES;
+                const bf16x8 vf = read_v_fragment(a);
                 bf16x8 tvf = vf;   // placeholder when there is no tV
-                if constexpr (!ZT)
-                    tvf = join_tr(lds_read_tr_b64(a + TENSOR_BYTES), lds_read_tr_b64(a + TENSOR_BYTES + 8 * ROW_BYTES));
+                if constexpr (!ZT) tvf = read_v_fragment(a + TENSOR_BYTES);
                 accO[db] = VMFMA(vf, pb, accO[db]);
                 if constexpr (!ZT) accAB[db] = VMFMA(tvf, pb, accAB[db]);
                 if constexpr (!PRIMAL) accAB[db] = VMFMA(vf, hb8, accAB[db]);
@@ -861,7 +899,7 @@ __device__ __forceinline__ void attn_jvp_tile(
     constexpr int KPRE = 3, KRING = KPRE + 1, VPRE = 2, VRING = VPRE + 1;
     constexpr int KFIRST = NG == 8 ? 2 : 1;   // value group after which the next iteration's first score fragments are requested
     static_assert(KPRE < NT && KFIRST + KPRE <= NG && VPRE < NG, "the fragment rings fit the key block's steps and groups");
-    const LaneOffsets lofs = make_lane_offsets<DH>(wave, lane, k_stride, v_stride);
+    const LaneOffsets lofs = make_lane_offsets<DH, F16>(wave, lane, k_stride, v_stride);
     const int n_full = Lkv / BC;                       // blocks that need no row clamping
     bf16x8 kfr[KRING], tkfr[KRING], vfr[VRING], tvfr[VRING];
     auto read_k = [&](auto T, auto ST) __attribute__((always_inline)) {     // score step T of the block in K stage ST
@@ -875,11 +913,10 @@ __device__ __forceinline__ void attn_jvp_tile(
     auto read_v = [&](auto Gi, auto ST) __attribute__((always_inline)) {    // value group Gi of the block in V stage ST
         constexpr int gi = decltype(Gi)::value;
         constexpr int t2 = gi / NDB, db = gi % NDB;
-        constexpr int off = decltype(ST)::value * KV_STAGE_BYTES + t2 * 16 * ROW_BYTES;
-        if constexpr (!ZT)
-            tvfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES),
-                                       lds_read_tr_b64(vaddr0[db] + off + TENSOR_BYTES + 8 * ROW_BYTES));
-        vfr[gi % VRING] = join_tr(lds_read_tr_b64(vaddr0[db] + off), lds_read_tr_b64(vaddr0[db] + off + 8 * ROW_BYTES));
+        constexpr int off = decltype(ST)::value * KV_STAGE_BYTES + (F16 ? db * (32 * 64) : t2 * 16 * ROW_BYTES);
+        const uint32_t a = vaddr0[F16 ? t2 : db] + off;
+        if constexpr (!ZT) tvfr[gi % VRING] = read_v_fragment(a + TENSOR_BYTES);
+        vfr[gi % VRING] = read_v_fragment(a);
     };
 
     // The copies of iteration b: K(b+4) into K stage b & 3, V(b+3) into V stage (b+3) & 3, as 8 direct-to-LDS
@@ -895,7 +932,10 @@ __device__ __forceinline__ void attn_jvp_tile(
         const char* base = which == 0 ? Kh : which == 1 ? tKh : which == 2 ? Vh : tVh;
         const uint32_t dst = lds0 + (which < 2 ? 0 : V_RING_BASE) + (uint32_t)(blk & 3) * KV_STAGE_BYTES +
                              (which & 1) * TENSOR_BYTES + (wave * G::COPIES_PER_WAVE + i) * 1024;
-        if constexpr (decltype(FULLc)::value) {
+        if constexpr (F16 && which >= 2) {                 // a whole transposed block of the fp16 copies: nothing to clamp but the block index
+            const int bc = decltype(FULLc)::value ? blk : (blk < n_blocks ? blk : n_blocks - 1);
+            load_lds_b128(base + (long)bc * TENSOR_BYTES, lofs.v[i], __builtin_amdgcn_readfirstlane(dst));
+        } else if constexpr (decltype(FULLc)::value) {
             const uint32_t lo = which < 2 ? lofs.k[i] : lofs.v[i];
             load_lds_b128(base + (long)blk * (BC * (which < 2 ? k_stride : v_stride)), lo, __builtin_amdgcn_readfirstlane(dst));
         } else {

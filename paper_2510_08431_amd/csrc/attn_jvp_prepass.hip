@@ -1,4 +1,4 @@
-// Pre-pass of the fp16 value path: per-head statistics, then V, tV -> scaled fp16 copies in the workspace.
+// Pre-pass of the fp16 value path: per-head statistics, then V, tV -> scaled, block-transposed fp16 copies in the workspace.
 // Two memory-bound launches (coalesced 128-bit accesses).  The first reads V and tV once (their largest magnitudes
 // fix the scales of the fp16 copies) and every 16th row of Q, tQ, K, tK (their row norms only steer how the tangent
 // weights are scaled; an estimate is enough, see f16_scales.h), and leaves one partial result per block; the second
@@ -111,17 +111,26 @@ __global__ __launch_bounds__(256) void head_stats_kernel(StatsArgs a, float* __r
 
 // Reduces the head's partial statistics (NaN in an input gives NaN here and ends in the bf16-pair fallback), leaves
 // them in stats[head * 8 ..] for the sweep kernels (block 0 of each head), clears the lock-step tickets (block 0 of
-// head 0), then converts its share of the head's V, tV rows.
+// head 0), then converts its share of the head's V, tV to scaled fp16, TRANSPOSED key block by key block, which is how
+// the sweep kernels want them: block j of a head is [DH][32] fp16, and within a row position 16 t2 + 8 g + t holds key
+// 32 j + 16 t2 + 4 g + (t & 3) + 8 (t >> 2) (the order in which a score MFMA leaves the keys in a lane's registers, so
+// that the matching operand of a value MFMA is 16 contiguous bytes); keys past Lkv are stored as zeros.
+// One key block per pass of the workgroup: 32 rows are read whole (16 bytes per lane), converted into an LDS tile
+// [key][DH + 4] (the padding spreads the transposed reads over the banks), and written out as 16-byte pieces.
 template <int DH>
 __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat16* __restrict__ V,
                                                              const __hip_bfloat16* __restrict__ tV,
                                                              const float* __restrict__ partials, int n_partials,
                                                              float* __restrict__ stats, float* __restrict__ tickets,
                                                              __half* __restrict__ V16,
-                                                             __half* __restrict__ tV16, long elems_per_head, float scale,
+                                                             __half* __restrict__ tV16, int n_blocks, float scale,
                                                              int Lkv, int H, int blhd) {
+    constexpr int LPR = DH / 8;              // 16-byte chunks per source row
+    constexpr int TILE_ROW = DH + 4;         // halves per row of the LDS tile
+    constexpr int IN_CHUNKS = 32 * LPR / 256, OUT_CHUNKS = DH * 4 / 256;   // per thread and tensor
     const long bh = blockIdx.y;
     __shared__ float head_stats[8];
+    __shared__ __half tile[2][32 * TILE_ROW];
     if (threadIdx.x < 64) {          // lane t % 8 of the first wave takes statistic t % 8 of every 8th partial
         const int which = threadIdx.x & 7;
         float best = 0.f;
@@ -142,25 +151,40 @@ __global__ __launch_bounds__(256) void convert_values_kernel(const __hip_bfloat1
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 128) tickets[threadIdx.x] = 0.f;
     __syncthreads();
     const F16Scales sc = f16_scales(head_stats, scale);
-    const float gV = ldexpf(1.f, -sc.eV), gT = ldexpf(1.f, -sc.eA);
-    const long base = bh * elems_per_head;
-    for (long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 8; i < elems_per_head; i += (long)gridDim.x * blockDim.x * 8) {
-        // i indexes the head's rows in [L,d] order (the order of the fp16 copies); the source row may be strided
-        const long src = row_offset<DH>(bh, (int)(i / DH), Lkv, H, blhd) + i % DH;
-        const uint4 a = *reinterpret_cast<const uint4*>(V + src);
-        const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
-        __half2 ao[4];
+    const float gain[2] = {ldexpf(1.f, -sc.eV), ldexpf(1.f, -sc.eA)};
+    const __hip_bfloat16* src[2] = {V, tV};
+    __half* dst[2] = {V16, tV16};
+    const int n_tensors = tV != nullptr ? 2 : 1;         // uniform: tV is absent when the caller passes no key/value tangents
+    for (int blk = blockIdx.x; blk < n_blocks; blk += gridDim.x) {
+        for (int x = 0; x < n_tensors; ++x) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) ao[j] = __floats2half2_rn(bf16_lo(aw[j]) * gV, bf16_hi(aw[j]) * gV);
-        *reinterpret_cast<uint4*>(V16 + base + i) = *reinterpret_cast<const uint4*>(ao);
-        if (tV != nullptr) {                  // uniform: absent when the caller passes no key/value tangents
-            const uint4 b = *reinterpret_cast<const uint4*>(tV + src);
-            const uint32_t bw[4] = {b.x, b.y, b.z, b.w};
-            __half2 bo[4];
+            for (int u = 0; u < IN_CHUNKS; ++u) {
+                const int q = threadIdx.x + 256 * u, row = q / LPR, sub = q % LPR;
+                const int key = blk * 32 + row;
+                uint4 a = make_uint4(0, 0, 0, 0);
+                if (key < Lkv) a = *reinterpret_cast<const uint4*>(src[x] + row_offset<DH>(bh, key, Lkv, H, blhd) + sub * 8);
+                const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+                alignas(16) __half2 h[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bo[j] = __floats2half2_rn(bf16_lo(bw[j]) * gT, bf16_hi(bw[j]) * gT);
-            *reinterpret_cast<uint4*>(tV16 + base + i) = *reinterpret_cast<const uint4*>(bo);
+                for (int j = 0; j < 4; ++j) h[j] = __floats2half2_rn(bf16_lo(aw[j]) * gain[x], bf16_hi(aw[j]) * gain[x]);
+                uint2* t = reinterpret_cast<uint2*>(&tile[x][row * TILE_ROW + sub * 8]);     // rows are 8-byte aligned
+                t[0] = reinterpret_cast<const uint2*>(h)[0];
+                t[1] = reinterpret_cast<const uint2*>(h)[1];
+            }
         }
+        __syncthreads();
+        for (int x = 0; x < n_tensors; ++x) {
+#pragma unroll
+            for (int u = 0; u < OUT_CHUNKS; ++u) {
+                const int o = threadIdx.x + 256 * u, col = o >> 2, chunk = o & 3;    // 16-byte piece `chunk` of row `col`
+                const int key0 = 16 * (chunk >> 1) + 4 * (chunk & 1);
+                alignas(16) __half v[8];
+#pragma unroll
+                for (int t = 0; t < 8; ++t) v[t] = tile[x][(key0 + (t & 3) + 8 * (t >> 2)) * TILE_ROW + col];
+                *reinterpret_cast<uint4*>(dst[x] + ((bh * n_blocks + blk) * (long)(32 * DH)) + o * 8) = *reinterpret_cast<const uint4*>(v);
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -177,7 +201,8 @@ Layout layout(int B, int H, int Lq, int Lkv, int d) {
     const int Lmax = Lq > Lkv ? Lq : Lkv;
     const int np = (Lmax + ROWS_PER_BLOCK - 1) / ROWS_PER_BLOCK;
     auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
-    return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)) + 512, up(heads * (size_t)Lkv * d * sizeof(__half)),
+    const size_t key_blocks = (size_t)((Lkv + 31) / 32);     // the fp16 copies are whole 32-key blocks
+    return {up(heads * 8 * sizeof(float)), up(tiles * sizeof(int)) + 512, up(heads * key_blocks * 32 * d * sizeof(__half)),
             up(heads * (size_t)np * 8 * sizeof(float)), np};
 }
 struct PadArgs {
@@ -273,16 +298,14 @@ hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out) {
         hipLaunchKernelGGL(head_stats_kernel<64>, dim3(l.n_partials, (unsigned)heads, 6), dim3(256), 0, p.stream, sa, partials);
     else
         hipLaunchKernelGGL(head_stats_kernel<128>, dim3(l.n_partials, (unsigned)heads, 6), dim3(256), 0, p.stream, sa, partials);
-    const long eph = (long)p.Lkv * p.d;
-    int cx = (int)((eph / 8 + 255) / 256);
-    if (cx > 512) cx = 512;
-    if (cx < 1) cx = 1;
+    const int n_blocks = (p.Lkv + 31) / 32;
+    int cx = n_blocks < 512 ? n_blocks : 512;
     if (p.d == 64)
         hipLaunchKernelGGL(convert_values_kernel<64>, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), partials,
-                           l.n_partials, stats, tickets, V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
+                           l.n_partials, stats, tickets, V16, tV16, n_blocks, p.scale, p.Lkv, p.H, p.layout);
     else
         hipLaunchKernelGGL(convert_values_kernel<128>, dim3(cx, (unsigned)heads), dim3(256), 0, p.stream, bf(p.v), bf(p.tv), partials,
-                           l.n_partials, stats, tickets, V16, tV16, eph, p.scale, p.Lkv, p.H, p.layout);
+                           l.n_partials, stats, tickets, V16, tV16, n_blocks, p.scale, p.Lkv, p.H, p.layout);
     out->stats = stats;
     out->wg_flags = wg_flags;
     out->v16 = V16;

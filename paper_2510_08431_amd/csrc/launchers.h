@@ -58,7 +58,8 @@ constexpr int MFMA_TILE_ROWS = 128;   // query rows per workgroup of the MFMA ke
 // fp16 value path: bytes of device scratch it needs, and the pre-pass that fills it.  Workspace layout, each part
 // rounded up to 256 bytes: per-head statistics (8 floats per head) | one int per MFMA workgroup (hand-over flags
 // between the launches of the fp16 path: sampled-reference fp16, online fp16, bf16 pairs) followed by 512 bytes of
-// lock-step tickets (one counter per XCD, 64 bytes apart) | scaled fp16 copy of V | scaled fp16 copy of tV | partial
+// lock-step tickets (one counter per XCD, 64 bytes apart) | scaled fp16 copy of V | scaled fp16 copy of tV (both as
+// whole 32-key blocks, each block transposed to [d][32]; see convert_values_kernel) | partial
 // statistics (8 floats per head and 1024-row block) that the pre-pass's first kernel hands to its second.
 struct F16Workspace {
     float* stats;

@@ -56,9 +56,9 @@ def test_opts_struct_layout_matches_header(tmp_path):
 def test_workspace_bytes(lib):
     lib.attn_jvp_workspace_bytes.restype = ctypes.c_size_t
     n = lib.attn_jvp_workspace_bytes(1, 12, 32760, 32760, 128)
-    # two fp16 copies + 12 x 32 B of statistics (rounded up to 256) + one int per 128-row query tile + 512 B of
+    # two fp16 copies (whole 32-key blocks: 32768 keys) + 12 x 32 B of statistics (rounded up to 256) + one int per 128-row query tile + 512 B of
     # lock-step tickets + 32 B of partial statistics per head and 1024-row block of the longer sequence
-    assert n == 2 * 12 * 32760 * 128 * 2 + 512 + 12 * 256 * 4 + 512 + 12 * 32 * 32
+    assert n == 2 * 12 * 32768 * 128 * 2 + 512 + 12 * 256 * 4 + 512 + 12 * 32 * 32
     pad = (2 * 2 * 256 * 128 * 2) + 4 * (2 * 256 * 128 * 2)           # zero-padded q, tq and k, v, tk, tv
     f16 = 2 * 2 * 256 * 128 * 2 + 256 + 256 + 512 + 256               # fp16 copies + statistics + 4 tile flags + tickets + partials
     assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 32) == pad + f16
