@@ -15,7 +15,8 @@
 // Key/value blocks (32 rows x 128 bf16 per tensor) are copied HBM -> LDS with 128-bit direct-to-LDS loads
 // into two rings of 4 stages each (K|tK: 16 KiB per stage, V|tV: 16 KiB per stage, 128 KiB in all), K four
 // blocks and V three blocks ahead of the block being accumulated, XOR-swizzled so that both the row-wise
-// 128-bit reads (K, tK as MFMA A operand) and the transposing 64-bit reads (V, tV) spread over all banks.
+// 128-bit reads (K, tK as MFMA A operand) and the transposing 64-bit reads (V, tV) spread over all banks.  (The fp16
+// copies of V, tV are stored transposed by the pre-pass, block by block, and are read row-wise like K.)
 // Q and tQ fragments stay in registers (in the AGPR half of the file: only MFMA instructions read them); they reach
 // them through LDS, and the results leave through LDS, so that every global load and store moves whole rows.
 //
