@@ -4,6 +4,7 @@ host pass, linked with the ordinary objects of the other sources, and the argume
 test_library_abi.py are run against that library in a child process with the sanitizer runtime preloaded: fake
 pointers, no GPU needed, every call must be answered on the host and neither sanitizer may report anything."""
 import os
+import shlex
 import subprocess
 import sys
 
@@ -42,14 +43,14 @@ def test_validation_cases_under_host_sanitizers(tmp_path):
         pytest.skip("no AddressSanitizer runtime in this toolchain")
     obj = str(tmp_path / "attn_jvp_api_san.o")
     lib = str(tmp_path / "libattn_jvp_san.so")
-    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fno-sanitize-recover=undefined"]
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-fPIC", "-std=c++17", "-Wno-unused-command-line-argument",
-                    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + san +
-                   ["-I", os.path.join(ROOT, "include"), "-c", os.path.join(ROOT, "paper_2510_08431_amd", "csrc", "attn_jvp_api.hip"),
-                    "-o", obj], check=True, capture_output=True)
-    subprocess.run([HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address", "-fsanitize=undefined", "-shared-libsan",
-                    "-fno-gpu-sanitize", "-o", lib, obj] + [os.path.join(BUILD, s + ".o") for s in OTHER_SOURCES],
-                   check=True, capture_output=True)
+    # (each command is one line of text, so that a reader, or a tool, sees at a glance that only the HOST pass is
+    # sanitized: every -fsanitize= of the compile line follows an -Xarch_host, the link line carries -fno-gpu-sanitize)
+    inc, src = os.path.join(ROOT, "include"), os.path.join(ROOT, "paper_2510_08431_amd", "csrc", "attn_jvp_api.hip")
+    compile_cmd = f"{HIPCC} --offload-arch=gfx950 -O1 -g -fPIC -std=c++17 -Wno-unused-command-line-argument -Xclang -target-feature -Xclang -packed-fp32-ops -Xarch_host -fsanitize=address -Xarch_host -fsanitize=undefined -Xarch_host -fno-sanitize-recover=undefined -I {inc} -c {src} -o {obj}"
+    others = " ".join(os.path.join(BUILD, s + ".o") for s in OTHER_SOURCES)
+    link_cmd = f"{HIPCC} --offload-arch=gfx950 -shared -fPIC -fno-gpu-sanitize -fsanitize=address -fsanitize=undefined -shared-libsan -o {lib} {obj} {others}"
+    subprocess.run(shlex.split(compile_cmd), check=True, capture_output=True)
+    subprocess.run(shlex.split(link_cmd), check=True, capture_output=True)
     env = dict(os.environ, LD_PRELOAD=runtime, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0:exitcode=99",
                UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1")
     res = subprocess.run([sys.executable, "-c", CHILD.format(root=ROOT, lib=lib)], env=env, capture_output=True, text=True,
