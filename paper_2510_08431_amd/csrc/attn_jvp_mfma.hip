@@ -1393,14 +1393,21 @@ static hipError_t launch_dh(const Problem& p_in) {
     const long long blocks = (long long)q_tiles * p.B * p.H;
     int lockstep = 0;   // set for the online launch below
     // The launch that does (nearly) all the tiles runs with resident workgroups, one per compute unit, each walking
-    // through its share of the tiles, when there are at least two tiles per unit; the hand-over launches, whose
-    // tiles differ in length or return at once, keep one workgroup per tile, which the hardware balances.
+    // through its share of the tiles, when there are at least two tiles per unit.  The hand-over launches do the
+    // same on sequences below LOCKSTEP_MIN_BLOCKS key blocks, without the staggered start: they usually find nothing
+    // to do, and a workgroup that looks at a dozen flags costs far less than a dozen workgroups that are launched
+    // (with all of a compute unit's LDS and registers each) to look at one (cross-attention workload: 13 + 9 us for
+    // the two launches with one workgroup per tile).  On longer sequences, where their tiles take milliseconds and
+    // differ in length, they keep one workgroup per tile, which the hardware balances.
     bool resident = false;
+    const bool short_tiles = (p.Lkv + BC - 1) / BC < LOCKSTEP_MIN_BLOCKS;
     auto launch = [&](auto kern, const void* v, const void* tv, const float* stats, int* wg_flags) -> hipError_t {
         constexpr int WG_PER_CU = DH == 64 ? 2 : 1;       // what the kernel's registers and LDS allow
-        const bool res = resident && cus % 8 == 0 && blocks >= 2LL * WG_PER_CU * cus && !(p.flags & 16);   // 16: ATTN_JVP_FLAG_NO_RESIDENT
+        const bool follower = !resident && wg_flags != nullptr;      // a hand-over launch of the fp16 path
+        const bool res = (resident || (follower && short_tiles)) && cus % 8 == 0 && blocks >= 2LL * WG_PER_CU * cus &&
+                         !(p.flags & 16);   // 16: ATTN_JVP_FLAG_NO_RESIDENT
         const long long grid = res ? (long long)WG_PER_CU * cus : blocks;
-        const int stagger = res ? STAGGER_TICKS : 0;
+        const int stagger = res && !follower ? STAGGER_TICKS : 0;
         hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(NTHREADS), Geo<DH>::LDS_BYTES, p.stream,
                            (const __hip_bfloat16*)p.q, (const __hip_bfloat16*)p.k, v,
                            (const __hip_bfloat16*)p.tq, (const __hip_bfloat16*)p.tk, tv,
