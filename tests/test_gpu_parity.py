@@ -680,6 +680,49 @@ def test_blhd_layout_gives_the_same_bits(case):
     compare(blhd, ref, dtype, f"[B,L,H,d] {case}", tol=FAST_TOL if case == "fast" else None)
 
 
+# ------------------------------------------------------------------ resident workgroups
+
+@pytest.mark.parametrize("case", ["f16", "bf16-pairs", "f16-declined-to-pairs", "f16-declined-to-online", "f16-null-kv", "f16-d64",
+                                  "pairs-d64"])
+def test_resident_workgroups_walk_their_tiles_like_one_workgroup_per_tile(case):
+    """With at least two query tiles per compute unit (four at head dimension 64) the sweep runs with resident workgroups
+    that walk through their tiles and request the next tile's first rows ahead of time; with short key sequences the
+    hand-over launches of the fp16 path do the same.  Nothing of that may change a bit: the outputs equal those of a
+    launch with one workgroup per tile (ATTN_JVP_FLAG_NO_RESIDENT), in both layouts, heads and tiles ragged; plus
+    oracle parity on rows at tile and head edges."""
+    cus = torch.cuda.get_device_properties(DEV).multi_processor_count
+    d = 64 if case.endswith("d64") else 128
+    Lq, Lkv = 1050, 300                                       # 9 tiles per head, the last one ragged; 10 key blocks, ragged
+    declined = case.startswith("f16-declined")
+    # enough heads for the resident launch; "declined-to-pairs" takes the fp16 path by the library's own rule (four tiles
+    # per compute unit), so that tiles it declines go to the pair launch, which then runs resident as well
+    per_cu = (2 if d == 64 else 1) * (4 if case == "f16-declined-to-pairs" else 2)
+    H = -(-(per_cu * cus + 8) // 9)
+    flags = (binding.FLAG_NO_F16 if case.startswith(("bf16-pairs", "pairs")) else
+             0 if case == "f16-declined-to-pairs" else binding.FLAG_F16_ALWAYS)
+    qk_gain = 6.0 ** 0.5 if declined else 1.0      # logit std 6: the sampled-reference kernel declines every tile
+    null_kv = case == "f16-null-kv"
+    t = random_inputs(4242 + len(case), 1, H, Lq, Lkv, d, torch.bfloat16, qk_gain=qk_gain)
+    if null_kv:
+        t["tk"].zero_(); t["tv"].zero_()
+    scale = d ** -0.5
+    run = (lambda f: run_gpu_no_kv_tangents(t, scale, binding.KERNEL_MFMA, f)) if null_kv else (lambda f: run_gpu(t, scale, binding.KERNEL_MFMA, f))
+    resident = run(flags)
+    if case.startswith("f16"):
+        fl = f16_tile_flags(1, H, Lq)
+        assert (fl == {"f16-declined-to-pairs": 2, "f16-declined-to-online": 3}.get(case, 0)).all(), fl
+    per_tile = run(flags | binding.FLAG_NO_RESIDENT)
+    blhd = run_gpu_blhd(t, scale, binding.KERNEL_MFMA, flags, null_kv)
+    for a, b, c, name in zip(resident, per_tile, blhd, ("o", "to", "lse")):
+        np.testing.assert_array_equal(a, b, err_msg=f"{case}: {name} differs between resident workgroups and one workgroup per tile")
+        np.testing.assert_array_equal(a, c, err_msg=f"{case}: {name} differs between the two layouts")
+    rows = np.array([0, 1, 127, 128, 129, 511, 512, 1023, 1024, 1048, 1049])
+    heads = [0, 1, H // 2, H - 1]
+    sub = {n: x[:, heads] for n, x in t.items()}
+    ref = attn_jvp_ref(sub["q"], sub["k"], sub["v"], sub["tq"], sub["tk"], sub["tv"], scale, rows=rows)
+    compare(tuple(x[:, heads] for x in resident), ref, torch.bfloat16, f"resident {case}", rows=rows)
+
+
 # ------------------------------------------------------------------ bf16 outputs
 
 @pytest.mark.parametrize("variant", list(VARIANTS) + ["fast"])
