@@ -680,6 +680,27 @@ def test_blhd_layout_gives_the_same_bits(case):
     compare(blhd, ref, dtype, f"[B,L,H,d] {case}", tol=FAST_TOL if case == "fast" else None)
 
 
+@pytest.mark.parametrize("case", ["std 2, 32760 keys", "std 3.5, 32760 keys", "cross-attention, 512 keys, no key/value tangents"])
+def test_f16_path_error_margin_over_seeds(case):
+    """The fp16 path's worst errors are those of single rows with few dominant keys, so they move with the inputs:
+    several seeds per case, every output element against the oracle, the worst figures printed (they are what the
+    design notes quote as the margin below the tolerances)."""
+    if case.startswith("cross"):
+        B, H, Lq, Lkv, ts, gain = 1, 4, 2048, 512, 0.5, 1.0
+    else:
+        B, H, Lq, Lkv, ts, gain = 1, 1, 256, 32760, 1.0, float(case.split()[1].rstrip(",")) ** 0.5
+    worst = np.zeros(3)
+    for seed in range(4):
+        t = random_inputs(100 + seed, B, H, Lq, Lkv, 128, torch.bfloat16, tangent_std=ts, qk_gain=gain)
+        if case.startswith("cross"):
+            t["tk"].zero_(); t["tv"].zero_()
+        ref = attn_jvp_ref(t["q"], t["k"], t["v"], t["tq"], t["tk"], t["tv"], 128 ** -0.5)
+        got = run_gpu(t, 128 ** -0.5, binding.KERNEL_MFMA, binding.FLAG_F16_ALWAYS)
+        e_o, e_to = compare(got, ref, torch.bfloat16, f"{case}, seed {seed}")
+        worst = np.maximum(worst, [e_o, e_to, np.abs(got[2] - ref[2]).max()])
+    print(f"[{case}] worst over 4 seeds: O={worst[0]:.2e} tO={worst[1]:.2e} lse={worst[2]:.2e}", flush=True)
+
+
 # ------------------------------------------------------------------ resident workgroups
 
 @pytest.mark.parametrize("case", ["f16", "bf16-pairs", "f16-declined-to-pairs", "f16-declined-to-online", "f16-null-kv", "f16-d64",
