@@ -144,9 +144,9 @@ typedef struct attn_jvp_opts {
                                enter the value contractions as single fp16 terms (6 matrix products per key block,
                                11-bit weights) against an exponent reference sampled before the sweep.  Query
                                tiles whose scores are too spread out for that (standard deviation of a row's
-                               scaled scores above ~3.3) are done by a second launch with a running reference.
+                               scaled scores above ~2.5) are done by a second launch with a running reference.
                                On this path the row sums are taken over the weights as rounded, so o, to are
-                               the exact result for probabilities and tangent scores off by 2^-11 relative, and
+                               the exact result for probabilities off by 2^-11 and centred tangent scores off by 2^-10 relative, and
                                lse carries the rounding of l (at most 2^-11 absolute).  Without a workspace, and for
                                Lkv < 2048 (Lkv < 256 for calls with at least four 128-row query tiles per compute
                                unit): hi + lo bf16 pairs everywhere (9 products, ~16-bit weights). */
@@ -164,8 +164,8 @@ typedef struct attn_jvp_opts {
  * Returns ATTN_JVP_OK or an error code above.
  * This call passes no workspace, so at d = 128 it runs the hi + lo bf16-pair kernel: 9 matrix products per key
  * block where the fp16 value path runs 6, i.e. about 1.35x the time on long key sequences (measured on the
- * 32760-token self-attention shape, B = 1, H = 12: 20.5-21.3 ms against 15.2-16.4 ms; 37-38 % against 48-52 % of the
- * bf16 matrix peak).  Callers that want the faster path lend a workspace through attn_jvp_fwd_ex, or call
+ * 32760-token self-attention shape, B = 1, H = 12: 20.4-21.4 ms against 14.7-15.7 ms; 37-39 % against 50-53 % of the
+ * bf16 matrix peak, over the boxes of one pool).  Callers that want the faster path lend a workspace through attn_jvp_fwd_ex, or call
  * attn_jvp_fwd_static, which brings its own.
  */
 int attn_jvp_fwd(const void* q, const void* k, const void* v,
