@@ -704,7 +704,7 @@ def test_f16_path_error_margin_over_seeds(case):
 # ------------------------------------------------------------------ resident workgroups
 
 @pytest.mark.parametrize("case", ["f16", "bf16-pairs", "f16-declined-to-pairs", "f16-declined-to-online", "f16-null-kv", "f16-d64",
-                                  "pairs-d64"])
+                                  "pairs-d64", "f16-five-keys"])
 def test_resident_workgroups_walk_their_tiles_like_one_workgroup_per_tile(case):
     """With at least two query tiles per compute unit (four at head dimension 64) the sweep runs with resident workgroups
     that walk through their tiles and request the next tile's first rows ahead of time; with short key sequences the
@@ -714,6 +714,8 @@ def test_resident_workgroups_walk_their_tiles_like_one_workgroup_per_tile(case):
     cus = torch.cuda.get_device_properties(DEV).multi_processor_count
     d = 64 if case.endswith("d64") else 128
     Lq, Lkv = 1050, 300                                       # 9 tiles per head, the last one ragged; 10 key blocks, ragged
+    if case == "f16-five-keys":
+        Lkv = 5                                               # (the rows requested ahead for the next tile's head stop at the last key)
     declined = case.startswith("f16-declined")
     # enough heads for the resident launch; "declined-to-pairs" takes the fp16 path by the library's own rule (four tiles
     # per compute unit), so that tiles it declines go to the pair launch, which then runs resident as well
