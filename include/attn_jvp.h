@@ -86,8 +86,8 @@ extern "C" {
 #define ATTN_JVP_KERNEL_MFMA 2    /* matrix-core kernels.
                                      bf16 inputs: scale > 0, d in {64, 128} (built natively); d in {32, 96} given a
                                      workspace of attn_jvp_workspace_bytes(...): the inputs are first copied there
-                                     zero-padded to 128 columns (exact: the padding adds zeros to every product; a
-                                     quarter or more of the matrix work is then spent on zeros).
+                                     zero-padded to 64 and 128 columns (exact: the padding adds zeros to every
+                                     product; half and a quarter of the matrix work are then spent on zeros).
                                      fp32 inputs: d in {32, 64, 96, 128}, any finite scale, fp32 outputs; fp32 operands
                                      and fp32 accumulation throughout (Alg. 2 as printed), no workspace, flags ignored.
                                      Accuracy contract of this path: l, r and the accumulators are fp32 running sums
@@ -208,8 +208,9 @@ size_t attn_jvp_static_scratch_bytes(void);
  * Bytes of scratch the MFMA kernel can use for this shape (0 if it has no use for any).  d = 128: the fp16 value
  * path's 2 fp16 copies of V and tV (Lkv rounded up to a multiple of 32 keys: they are kept as whole 32-key blocks), 32 bytes of statistics per (batch, head), 4 bytes per 128-row query tile and
  * 32 bytes per (batch, head) and 1024 rows of the longer sequence, each part rounded up to 256 bytes, and 512 bytes
- * of counters (d = 64 likewise, with its own row width).  d in {32, 96}: in front of that, zero-padded [.,128] bf16 copies of the
- * six inputs (without them the MFMA kernel does not take these head dimensions).  Pure host arithmetic.
+ * of counters (d = 64 likewise, with its own row width).  d in {32, 96}: in front of that, bf16 copies of the six inputs
+ * zero-padded to 64 and 128 columns (without them the MFMA kernel does not take these head dimensions), and the
+ * rest sized for the padded width.  Pure host arithmetic.
  */
 size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 

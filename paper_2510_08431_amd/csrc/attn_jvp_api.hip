@@ -184,7 +184,7 @@ size_t attn_jvp_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
     if (B <= 0 || H <= 0 || Lq <= 0 || Lkv <= 0) return 0;
     if (d != 128 && d != 32 && d != 64 && d != 96) return 0;
     if (d == 32 || d == 96)                 // zero-padded copies of the inputs in front of the fp16 path's scratch
-        return attn_jvp::pad_workspace_bytes(B, H, Lq, Lkv) + attn_jvp::f16_workspace_bytes(B, H, Lq, Lkv, attn_jvp::MFMA_HEAD_DIM);
+        return attn_jvp::pad_workspace_bytes(B, H, Lq, Lkv, d) + attn_jvp::f16_workspace_bytes(B, H, Lq, Lkv, attn_jvp::padded_head_dim_of(d));
     return attn_jvp::f16_workspace_bytes(B, H, Lq, Lkv, d);
 }
 

@@ -1344,12 +1344,12 @@ __global__ __launch_bounds__(NTHREADS, DH == 64 ? 2 : 1) void attn_jvp_mfma_kern
 // scale > 0: the kernel masks padded keys with a raw score of -inf and takes row maxima before scaling.
 // tk and tv are either both given or both absent (zero key/value tangents); single bf16 weights (FAST) are not built
 // for the latter.
-// Head dimensions 128 and 64 are built natively; 32 and 96 run on zero-padded copies (to 128 columns), which need the
-// caller's workspace.
+// Head dimensions 128 and 64 are built natively; 32 and 96 run on zero-padded copies (to 64 and 128 columns), which
+// need the caller's workspace.
 static bool padded_head_dim(const Problem& p) {
     return (p.d == 32 || p.d == 96) && p.workspace != nullptr &&
            (reinterpret_cast<uintptr_t>(p.workspace) & 255u) == 0 &&
-           p.workspace_bytes >= pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv);
+           p.workspace_bytes >= pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv, p.d);
 }
 bool mfma_bf16_supports(const Problem& p) {
     const bool zt = p.tk == nullptr && p.tv == nullptr;     // (the API admits absent tangents only as tk+tv or tq+tk+tv)
@@ -1462,7 +1462,7 @@ static hipError_t launch_dh(const Problem& p_in) {
 
 hipError_t launch_mfma_bf16(const Problem& p) {
     if (!mfma_bf16_supports(p)) return hipErrorInvalidValue;
-    return p.d == 64 ? launch_dh<64>(p) : launch_dh<128>(p);
+    return p.d <= 64 ? launch_dh<64>(p) : launch_dh<128>(p);     // 32 runs on copies padded to 64 columns, 96 to 128
 }
 
 }  // namespace attn_jvp

@@ -12,7 +12,6 @@
 namespace attn_jvp {
 namespace {
 
-constexpr int D = 128;                   // width of the zero-padded copies
 constexpr int ROWS_PER_BLOCK = 1024;     // rows of a tensor one block of the statistics kernel looks at
 
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -210,17 +209,19 @@ struct PadArgs {
     __hip_bfloat16* dst[6];
     int L[6];
     int H, d, blhd;
+    int D;                          // width of the zero-padded copies (64 or 128)
 };
 
-// dst[B,H,L,128] = src rows (any layout) followed by zeros.  One thread per 16-byte chunk of dst; blockIdx.z = tensor.
+// dst[B,H,L,D] = src rows (any layout) followed by zeros.  One thread per 16-byte chunk of dst; blockIdx.z = tensor.
 __global__ __launch_bounds__(256) void pad_inputs_kernel(PadArgs a, long heads) {
     const int which = blockIdx.z;
     if (a.src[which] == nullptr) return;
     const int L = a.L[which];
-    const long n_chunks = heads * L * (D / 8);
+    const int cpr = a.D / 8;                    // chunks per padded row
+    const long n_chunks = heads * L * cpr;
     for (long i = (long)blockIdx.x * blockDim.x + threadIdx.x; i < n_chunks; i += (long)gridDim.x * blockDim.x) {
-        const int c = (int)(i % (D / 8));
-        const long hr = i / (D / 8);            // head * L + row
+        const int c = (int)(i % cpr);
+        const long hr = i / cpr;                // head * L + row
         const long bh = hr / L;
         const int row = (int)(hr % L);
         uint4 v = make_uint4(0, 0, 0, 0);
@@ -234,14 +235,14 @@ __global__ __launch_bounds__(256) void pad_inputs_kernel(PadArgs a, long heads) 
 
 }  // namespace
 
-size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv) {
-    const size_t heads = (size_t)B * H;
+size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv, int d) {
+    const size_t heads = (size_t)B * H, D = (size_t)padded_head_dim_of(d);
     auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
     return 2 * up(heads * Lq * D * 2) + 4 * up(heads * Lkv * D * 2);
 }
 
 hipError_t launch_pad_inputs(const Problem& p, Problem* padded) {
-    const size_t heads = (size_t)p.B * p.H;
+    const size_t heads = (size_t)p.B * p.H, D = (size_t)padded_head_dim_of(p.d);
     auto up = [](size_t n) { return (n + 255) & ~(size_t)255; };
     const size_t qb = up(heads * p.Lq * D * 2), kb = up(heads * p.Lkv * D * 2);
     char* ws = static_cast<char*>(p.workspace);
@@ -253,18 +254,18 @@ hipError_t launch_pad_inputs(const Problem& p, Problem* padded) {
         a.dst[i] = reinterpret_cast<__hip_bfloat16*>(ws + offs[i]);
         a.L[i] = (i == 0 || i == 3) ? p.Lq : p.Lkv;
     }
-    a.H = p.H; a.d = p.d; a.blhd = p.layout;
+    a.H = p.H; a.d = p.d; a.blhd = p.layout; a.D = (int)D;
     const int Lmax = p.Lq > p.Lkv ? p.Lq : p.Lkv;
-    long blocks = ((long)heads * Lmax * (D / 8) + 255) / 256;
+    long blocks = ((long)heads * Lmax * (long)(D / 8) + 255) / 256;
     if (blocks > 8192) blocks = 8192;
     hipLaunchKernelGGL(pad_inputs_kernel, dim3((unsigned)blocks, 1, 6), dim3(256), 0, p.stream, a, (long)heads);
     *padded = p;
     auto at = [&](int i) -> const void* { return srcs[i] ? static_cast<const void*>(a.dst[i]) : nullptr; };
     padded->q = at(0); padded->k = at(1); padded->v = at(2); padded->tq = at(3); padded->tk = at(4); padded->tv = at(5);
-    padded->d = D;
+    padded->d = (int)D;
     padded->layout = 0;
-    padded->workspace = ws + pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv);
-    padded->workspace_bytes = p.workspace_bytes - pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv);
+    padded->workspace = ws + pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv, p.d);
+    padded->workspace_bytes = p.workspace_bytes - pad_workspace_bytes(p.B, p.H, p.Lq, p.Lkv, p.d);
     return hipGetLastError();
 }
 

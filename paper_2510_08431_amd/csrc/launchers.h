@@ -70,11 +70,12 @@ struct F16Workspace {
 };
 size_t f16_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 
-// Head dimensions below 128 on the MFMA kernel: the inputs are first copied, zero-padded to 128 columns, into the
-// front of the workspace ([B,H,L,128] bf16 each, absent tangents skipped); the padded columns add exact zeros to
-// every product.  Bytes of that area, and the copy.
+// Head dimensions the MFMA kernel is not built for (32 and 96): the inputs are first copied, zero-padded to the next
+// width it is built for (64 and 128 columns), into the front of the workspace ([B,H,L,width] bf16 each, absent
+// tangents skipped); the padded columns add exact zeros to every product.  Width, bytes of that area, and the copy.
 constexpr int MFMA_HEAD_DIM = 128;
-size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv);
+inline int padded_head_dim_of(int d) { return d <= 64 ? 64 : MFMA_HEAD_DIM; }
+size_t pad_workspace_bytes(int B, int H, int Lq, int Lkv, int d);
 hipError_t launch_pad_inputs(const Problem& p, Problem* padded);
 hipError_t launch_f16_prepass(const Problem& p, int cus, F16Workspace* out);
 

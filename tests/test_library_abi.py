@@ -59,9 +59,10 @@ def test_workspace_bytes(lib):
     # two fp16 copies (whole 32-key blocks: 32768 keys) + 12 x 32 B of statistics (rounded up to 256) + one int per 128-row query tile + 512 B of
     # lock-step tickets + 32 B of partial statistics per head and 1024-row block of the longer sequence
     assert n == 2 * 12 * 32768 * 128 * 2 + 512 + 12 * 256 * 4 + 512 + 12 * 32 * 32
-    pad = (2 * 2 * 256 * 128 * 2) + 4 * (2 * 256 * 128 * 2)           # zero-padded q, tq and k, v, tk, tv
-    f16 = 2 * 2 * 256 * 128 * 2 + 256 + 256 + 512 + 256               # fp16 copies + statistics + 4 tile flags + tickets + partials
-    assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 32) == pad + f16
+    for d, width in ((32, 64), (96, 128)):                             # padded to the next width the MFMA kernel is built for
+        pad = (2 * 2 * 256 * width * 2) + 4 * (2 * 256 * width * 2)   # zero-padded q, tq and k, v, tk, tv
+        f16 = 2 * 2 * 256 * width * 2 + 256 + 256 + 512 + 256         # fp16 copies + statistics + 4 tile flags + tickets + partials
+        assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, d) == pad + f16
     assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 64) == 2 * 2 * 256 * 64 * 2 + 256 + 256 + 512 + 256   # built natively: no padded copies
     assert lib.attn_jvp_workspace_bytes(1, 2, 256, 256, 48) == 0      # the MFMA kernel has no use for d = 48
     assert lib.attn_jvp_workspace_bytes(0, 2, 256, 256, 128) == 0
