@@ -217,3 +217,29 @@ def test_workload_shapes_match_configs():
     assert all((h[k] == h2[k]).all() for k in h)          # seeded: reproducible
     rows = sample_rows(CONFIGS[3], 64)
     assert rows.min() == 0 and rows.max() == 32759 and len(set(rows.tolist())) == len(rows)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; any other --gpus value ends with a message and a non-zero status before anything
+    touches a GPU (so this runs anywhere)."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    res = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert res.returncode != 0
+    assert "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_product_path_does_not_reach_the_oracle():
+    """Nothing under the package, and nothing in bench.py outside its CPU-baseline leg, imports the test oracle."""
+    import re
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    pkg = os.path.join(root, "paper_2510_08431_amd")
+    for name in os.listdir(pkg):
+        if name.endswith(".py"):
+            assert not re.search(r"^\s*(from|import)\s+oracle\b", open(os.path.join(pkg, name)).read(), re.M), name
+    bench = open(os.path.join(root, "bench.py")).read()
+    imports = [m.start() for m in re.finditer(r"^\s*(from|import)\s+oracle\b", bench, re.M)]
+    assert len(imports) == 2           # the attention oracle and the RMSNorm oracle, each inside `if not args.no_cpu_baseline`
+    for pos in imports:
+        assert "no_cpu_baseline" in bench[max(0, pos - 600):pos]
