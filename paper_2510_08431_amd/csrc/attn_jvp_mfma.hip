@@ -1337,6 +1337,9 @@ __global__ __launch_bounds__(NTHREADS, DH == 64 ? 2 : 1) void attn_jvp_mfma_kern
     for (int vw = blockIdx.x; vw < n_tiles; vw += gridDim.x)
         attn_jvp_tile<MODE, TAN, DH>(Q, K, V, tQ, tK, tV, O, tO, LSE, Lq, Lkv, scale, q_tiles, stats, wg_flags, H, blhd, out_bf16,
                                  d_out, out_blhd, online_min_blocks, lockstep_slots, vw, n_tiles);
+    // (a hand-over launch may have requested lines for a next tile that turned out not to be its own: no direct-to-LDS
+    // load is left in flight when the wave ends)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
 
 }  // namespace

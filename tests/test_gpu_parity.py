@@ -704,7 +704,7 @@ def test_f16_path_error_margin_over_seeds(case):
 # ------------------------------------------------------------------ resident workgroups
 
 @pytest.mark.parametrize("case", ["f16", "bf16-pairs", "f16-declined-to-pairs", "f16-declined-to-online", "f16-null-kv", "f16-d64",
-                                  "pairs-d64", "f16-five-keys"])
+                                  "pairs-d64", "f16-five-keys", "f16-mixed-heads"])
 def test_resident_workgroups_walk_their_tiles_like_one_workgroup_per_tile(case):
     """With at least two query tiles per compute unit (four at head dimension 64) the sweep runs with resident workgroups
     that walk through their tiles and request the next tile's first rows ahead of time; with short key sequences the
@@ -719,21 +719,28 @@ def test_resident_workgroups_walk_their_tiles_like_one_workgroup_per_tile(case):
     declined = case.startswith("f16-declined")
     # enough heads for the resident launch; "declined-to-pairs" takes the fp16 path by the library's own rule (four tiles
     # per compute unit), so that tiles it declines go to the pair launch, which then runs resident as well
-    per_cu = (2 if d == 64 else 1) * (4 if case == "f16-declined-to-pairs" else 2)
+    mixed = case == "f16-mixed-heads"      # every other head declined: the pair launch's workgroups find their tiles between others'
+    per_cu = (2 if d == 64 else 1) * (4 if case == "f16-declined-to-pairs" or mixed else 2)
     H = -(-(per_cu * cus + 8) // 9)
     flags = (binding.FLAG_NO_F16 if case.startswith(("bf16-pairs", "pairs")) else
-             0 if case == "f16-declined-to-pairs" else binding.FLAG_F16_ALWAYS)
+             0 if case == "f16-declined-to-pairs" or mixed else binding.FLAG_F16_ALWAYS)
     qk_gain = 6.0 ** 0.5 if declined else 1.0      # logit std 6: the sampled-reference kernel declines every tile
     null_kv = case == "f16-null-kv"
     t = random_inputs(4242 + len(case), 1, H, Lq, Lkv, d, torch.bfloat16, qk_gain=qk_gain)
     if null_kv:
         t["tk"].zero_(); t["tv"].zero_()
+    if mixed:
+        t["q"][:, 1::2] *= 6.0 ** 0.5
+        t["k"][:, 1::2] *= 6.0 ** 0.5
     scale = d ** -0.5
     run = (lambda f: run_gpu_no_kv_tangents(t, scale, binding.KERNEL_MFMA, f)) if null_kv else (lambda f: run_gpu(t, scale, binding.KERNEL_MFMA, f))
     resident = run(flags)
     if case.startswith("f16"):
         fl = f16_tile_flags(1, H, Lq)
-        assert (fl == {"f16-declined-to-pairs": 2, "f16-declined-to-online": 3}.get(case, 0)).all(), fl
+        if mixed:
+            assert (fl[0::2] == 0).all() and (fl[1::2] == 2).all(), fl
+        else:
+            assert (fl == {"f16-declined-to-pairs": 2, "f16-declined-to-online": 3}.get(case, 0)).all(), fl
     per_tile = run(flags | binding.FLAG_NO_RESIDENT)
     blhd = run_gpu_blhd(t, scale, binding.KERNEL_MFMA, flags, null_kv)
     for a, b, c, name in zip(resident, per_tile, blhd, ("o", "to", "lse")):
