@@ -106,3 +106,41 @@ def test_static_scratch_rejects_what_does_not_fit():
     vp = ctypes.c_void_p
     rc = lib.attn_jvp_fwd_static(*[vp(x.data_ptr())] * 9, B, H, L, L, d, ctypes.c_float(0.1), None)
     assert rc == 6 and "static" in binding.attn_jvp_strerror(rc)
+
+
+def test_static_entry_point_captured_in_a_hip_graph():
+    """What the entry point is for: a caller under HIP graph capture cannot allocate.  The call is captured (kernel
+    launches only: no allocation, no memset node, no attribute or symbol look-up, all of which the warm-up call
+    before the capture has done) and replayed several times on changing inputs, with eager work and synchronisations
+    between the replays; every replay must equal an eager call with a lent workspace bit for bit."""
+    lib = binding.load_library()
+    B, H, Lq, Lkv, d = 1, 2, 300, 2100, 128            # fp16 value path (2100 keys), ragged tiles and key blocks
+    scale = d ** -0.5
+    sets = [_inputs(31, B, H, Lq, Lkv, d), _inputs(32, B, H, Lq, Lkv, d, qk_gain=2.0)]
+    dev = {n: x.to(DEV) for n, x in sets[0].items()}   # the graph's fixed input buffers
+    out = (torch.empty(B, H, Lq, d, device=DEV), torch.empty(B, H, Lq, d, device=DEV), torch.empty(B, H, Lq, device=DEV))
+    side = torch.cuda.Stream(DEV)
+    opts = binding.AttnJvpOpts()
+    opts.stream = side.cuda_stream
+    with torch.cuda.stream(side):
+        _call_c(lib.attn_jvp_fwd_static, dev, out, (B, H, Lq, Lkv, d), scale, opts)      # warm-up, eager
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        _call_c(lib.attn_jvp_fwd_static, dev, out, (B, H, Lq, Lkv, d), scale, opts)
+    torch.cuda.synchronize()
+    ws = torch.empty(binding.attn_jvp_workspace_bytes(B, H, Lq, Lkv, d), dtype=torch.uint8, device=DEV)
+    for rep in range(4):
+        t = sets[rep % 2]
+        for n in dev:
+            dev[n].copy_(t[n])                         # eager work between the replays
+        for x in out:
+            x.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in out]
+        eager = binding.attn_jvp_fwd_ex(dev["q"], dev["k"], dev["v"], dev["tq"], dev["tk"], dev["tv"], scale, workspace=ws)
+        torch.cuda.synchronize()
+        for a, b, name in zip(got, eager, ("o", "to", "lse")):
+            assert torch.equal(a, b), f"replay {rep}: {name} differs from the eager call"
